@@ -1,0 +1,36 @@
+"""Kernel-selection formula of the paper (Sec. 4.2.3, Eq. 1) -- TEST INFRASTRUCTURE ONLY.
+
+    n         = ceil(seq_len / 16)
+    threshold = valid16 / n^2  -  tau / (log2 n)^2,      tau = 1.2
+
+valid16 = number of non-empty 16 x 16 tiles of the mask (load_row_ptr[n] of the
+block format at tile size 16).  The row-wise kernel is chosen iff threshold < 0.
+For n = 1 the logarithm is 0 and the formula is undefined; this build reads that
+case as "row-wise" (one tile, nothing to block).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+TAU = 1.2
+
+
+def valid16(M: np.ndarray) -> int:
+    S = M.shape[0]
+    n = -(-S // 16)
+    P = np.zeros((n * 16, n * 16), dtype=np.uint8)
+    P[:S, :S] = (M != 0)
+    return int((P.reshape(n, 16, n, 16).sum(axis=(1, 3)) > 0).sum())
+
+
+def threshold(valid: int, S: int, tau: float = TAU) -> float:
+    n = -(-S // 16)
+    if n <= 1:
+        return -math.inf
+    return valid / float(n * n) - tau / (math.log2(n) ** 2)
+
+
+def choose(valid: int, S: int, tau: float = TAU) -> str:
+    return "row" if threshold(valid, S, tau) < 0 else "block"
