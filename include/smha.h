@@ -1,0 +1,191 @@
+/*
+ * smha -- masked multi-head attention for AMD MI355X (gfx950), C ABI.
+ *
+ *   O = softmax(scale * Q K^T  restricted to the unmasked keys of each query) V
+ *
+ * computed only over the unmasked entries of a static mask.  The library follows the
+ * "unified MHA module" of the STOF paper (Sec. 4.2): a mask is analysed once into a
+ * per-row column-index format and a two-level block format (block-compressed sparse rows
+ * plus a bitmap per partially filled tile, Sec. 4.2.1), an analytical selector
+ * (Sec. 4.2.3, Eq. 1) picks a row-wise or a block-wise kernel, and the forward call runs
+ * one fused kernel that never touches empty tiles (Sec. 4.2.2, Algorithm 1).
+ *
+ * Conventions
+ *   - A mask entry of 1 means "query i attends key j".  A query with no unmasked key
+ *     produces an all-zero output row (the paper does not define this case).
+ *   - Sq = Sk = S.  head_dim d is 64 or 128.  Q/K/V are IEEE binary16 or bfloat16.
+ *   - All functions return a status code; nothing is printed, thrown or aborted.
+ *     On error, output parameters are left untouched.
+ *   - "host" / "device" is stated per pointer.  The library never frees or keeps
+ *     Q/K/V/O; it owns everything reachable from a plan.
+ */
+#ifndef SMHA_H
+#define SMHA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct smha_plan smha_plan_t; /* opaque; created by smha_plan_from_*, freed by smha_plan_destroy */
+
+typedef enum {
+    SMHA_OK = 0,
+    SMHA_ERR_INVALID_ARG = 1, /* null pointer, negative size, unknown enum value            */
+    SMHA_ERR_UNSUPPORTED = 2, /* head_dim / block size / dtype / alignment not supported    */
+    SMHA_ERR_SHAPE = 3,       /* B/H do not match the plan's mask broadcast shape, S < 1    */
+    SMHA_ERR_ALLOC = 4,       /* host or device allocation failed                           */
+    SMHA_ERR_HIP = 5          /* no usable GPU, or a HIP runtime call failed                */
+} smha_status_t;
+
+typedef enum { SMHA_F16 = 0, SMHA_BF16 = 1, SMHA_F32 = 2 /* output only */ } smha_dtype_t;
+typedef enum { SMHA_KERNEL_AUTO = 0, SMHA_KERNEL_ROW = 1, SMHA_KERNEL_BLOCK = 2 } smha_kernel_t;
+typedef enum {
+    SMHA_SELECTOR_CALIBRATED = 0, /* cost model fitted to MI355X measurements (default)       */
+    SMHA_SELECTOR_PAPER_EQ1 = 1   /* the paper's formula verbatim (Sec. 4.2.3, Eq. 1)         */
+} smha_selector_t;
+
+/* Plan options.  Zero-initialise for defaults. */
+typedef struct {
+    int block;      /* tile edge of the exported block format: 16, 32 or 64; 0 = 64 (the paper's
+                       OuterTile, Sec. 4.2.1)                                                  */
+    int force;      /* smha_kernel_t; AUTO lets the selector decide                            */
+    int selector;   /* smha_selector_t                                                         */
+    int build_both; /* nonzero: keep both formats so either kernel can be forced at run time  */
+    int device_id;  /* >= 0: upload index arrays to that GPU at plan time; -1: the current
+                       device if there is one, otherwise stay host-only (forward then returns
+                       SMHA_ERR_HIP); -2: host-only on purpose                                 */
+    int head_dim;   /* hint for the calibrated selector (0 = 64)                               */
+} smha_plan_opts_t;
+
+/* Mask description: the atomic patterns of the paper (Sec. 2.1.2, Fig. 1) and their
+ * compounds.  Composition:
+ *     M = (WINDOW | GLOBAL | STRIDED | BLOCK_RANDOM | BIGBIRD   [all ones if none is set])
+ *         & CAUSAL (if set) & PADDING (if set)
+ * Random components use a counter-based generator: u = top 53 bits of
+ * mix(mix(seed ^ mix(head)) ^ (block_row << 32 | block_col)) / 2^53 with mix = the
+ * splitmix64 output function, head = 0 unless per_head. */
+enum {
+    SMHA_MASK_CAUSAL = 1,        /* keep j <= i                                                */
+    SMHA_MASK_WINDOW = 2,        /* keep i - j <= window_left and j - i <= window_right        */
+    SMHA_MASK_GLOBAL = 4,        /* keep rows i < n_global and columns j < n_global            */
+    SMHA_MASK_STRIDED = 8,       /* keep j % stride == stride_phase                            */
+    SMHA_MASK_BLOCK_RANDOM = 16, /* keep block (br, bc) iff u < keep_p, and every br == bc     */
+    SMHA_MASK_BIGBIRD = 32,      /* per block row: n_window_blocks columns centred on br,
+                                    the first n_global_blocks block rows and columns, and the
+                                    n_random_blocks not-yet-kept columns of smallest (hash, bc) */
+    SMHA_MASK_PADDING = 64       /* keep only i < valid_len[b] and j < valid_len[b]            */
+};
+
+typedef struct {
+    uint32_t flags;
+    int window_left, window_right;
+    int n_global;
+    int stride, stride_phase;
+    int block; /* block edge of BLOCK_RANDOM / BIGBIRD (any positive size)                    */
+    double keep_p;
+    int n_window_blocks, n_global_blocks, n_random_blocks;
+    uint64_t seed;
+    int per_head;             /* random components differ per head: one mask per head          */
+    const int32_t *valid_len; /* host, [B]; required with PADDING: one mask per batch entry    */
+} smha_mask_desc_t;
+
+typedef struct {
+    int S, Bm, Hm;      /* sequence length; masks are [Bm][Hm][S][S], Bm in {1,B}, Hm in {1,H} */
+    int block;          /* tile edge of the exported block format                               */
+    int kernel;         /* SMHA_KERNEL_ROW or SMHA_KERNEL_BLOCK: what smha_forward will run     */
+    int has_row_format, has_block_kernel_lists, on_device;
+    int64_t nnz;        /* unmasked entries, summed over the Bm*Hm masks                         */
+    int64_t n_valid, n_full, n_part; /* tiles of edge `block`, summed over masks                 */
+    int64_t n_valid16;  /* non-empty 16x16 tiles, summed over masks (input of Eq. 1)             */
+    int64_t n_tiles64;  /* non-empty 64x64 tiles the block kernel visits, summed over masks      */
+    int64_t n_items, n_split_rows; /* block-kernel work items / query tiles split along keys     */
+    double eq1_threshold; /* Eq. 1 with valid16 averaged over masks; < 0 means row-wise          */
+    double model_row_us, model_block_us; /* calibrated cost model, per (batch, head) pair         */
+} smha_plan_info_t;
+
+/* Arrays smha_plan_export can copy out (all host byte order, packed):
+ *   ROW_PTR int32[S+1], COL_IDX int32[nnz]  -- per-row format, columns ascending in a row
+ *   LOAD/FULL/PART_ROW_PTR int32[nbr+1], LOAD/FULL/PART_COL_IDX int32[...]  (Sec. 4.2.1;
+ *     nbr = ceil(S/block); load = full U part, ascending inside a tile row)
+ *   BLOCK_FLAGS uint8 per load entry: 1 = full (all block*block entries unmasked), 0 = part
+ *   BITMAP uint64[n_part][block], part tiles in PART_COL_IDX order: word r = tile row r,
+ *     bit c (LSB = 0) = tile column c; entries past S are 0, so a ragged tile is never full
+ *   BITMAP_IT8 uint64[n_part][64] (block == 64 only): the paper's inner-tile layout, word
+ *     ic*8+ir = 8x8 inner tile (ir, ic) (column-major over inner tiles), bit 8*r+c = entry (r,c)
+ */
+typedef enum {
+    SMHA_EXPORT_ROW_PTR = 0,
+    SMHA_EXPORT_COL_IDX = 1,
+    SMHA_EXPORT_LOAD_ROW_PTR = 2,
+    SMHA_EXPORT_LOAD_COL_IDX = 3,
+    SMHA_EXPORT_BLOCK_FLAGS = 4,
+    SMHA_EXPORT_BITMAP = 5,
+    SMHA_EXPORT_FULL_ROW_PTR = 6,
+    SMHA_EXPORT_FULL_COL_IDX = 7,
+    SMHA_EXPORT_PART_ROW_PTR = 8,
+    SMHA_EXPORT_PART_COL_IDX = 9,
+    SMHA_EXPORT_BITMAP_IT8 = 10
+} smha_export_t;
+
+/* Mask analysis (Sec. 4.2.1) from a dense boolean mask.
+ *   mask            uint8 [Bm][Hm][S][S], nonzero = attend; host pointer if mask_on_device
+ *                   is 0, else a device pointer on the current device (the scan then runs
+ *                   on the GPU; the call synchronises before returning)
+ *   opts            may be NULL (defaults)
+ *   out             receives the plan
+ * Errors: INVALID_ARG (null, Bm/Hm/S < 1), UNSUPPORTED (block), ALLOC, HIP. */
+smha_status_t smha_plan_from_dense(const uint8_t *mask, int mask_on_device, int Bm, int Hm, int S,
+                                   const smha_plan_opts_t *opts, smha_plan_t **out);
+
+/* Mask analysis from a pattern description; B and H fix how many distinct masks exist
+ * (Bm = B with PADDING else 1; Hm = H with per_head and a random component, else 1). */
+smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B, int H, int S,
+                                  const smha_plan_opts_t *opts, smha_plan_t **out);
+
+smha_status_t smha_plan_info(const smha_plan_t *plan, smha_plan_info_t *out);
+
+/* Copy one index array of mask `mask_index` (= bm*Hm + hm) to host memory.
+ * *need receives the size in bytes; if cap < *need nothing is copied and the call still
+ * returns SMHA_OK (query-then-copy).  host_dst may be NULL when cap is 0.
+ * UNSUPPORTED if the plan does not hold that array (e.g. ROW_PTR of a block-only plan). */
+smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_export_t which,
+                               void *host_dst, size_t cap, size_t *need);
+
+/* Fused masked attention (Sec. 4.2.2, Algorithm 1 for the block kernel; Sec. 4.1 for the
+ * row-wise kernel).  Enqueues on `hip_stream` (a hipStream_t, NULL = default stream) and
+ * returns without synchronising.
+ *   Q, K, V         device, [B][H][S][d] of in_dtype, addressed through *_strides
+ *   O               device, [B][H][S][d] of out_dtype (same as in_dtype, or SMHA_F32)
+ *   *_strides       host, {batch, head, seq} strides in elements, d is contiguous;
+ *                   NULL = packed.  Pointers must be 16-byte aligned and strides multiples
+ *                   of 8 elements (UNSUPPORTED otherwise).
+ *   scale           <= 0 selects 1/sqrt(d)
+ *   kernel          AUTO = the plan's choice; ROW/BLOCK need that format in the plan
+ * The plan is read-only here except for a scratch buffer the block kernel uses when a
+ * query tile is split along keys; it is grown (hipMalloc) on the first call that needs
+ * more room, so two forwards on one plan must not overlap on different streams, and a
+ * call that may grow it must not be captured into a HIP graph (warm up once first).
+ * Errors: INVALID_ARG, UNSUPPORTED (d, dtype, alignment, missing format), SHAPE, ALLOC, HIP. */
+smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K, const void *V,
+                           void *O, int B, int H, int d, smha_dtype_t in_dtype,
+                           smha_dtype_t out_dtype, const int64_t q_strides[3],
+                           const int64_t k_strides[3], const int64_t v_strides[3],
+                           const int64_t o_strides[3], float scale, smha_kernel_t kernel,
+                           void *hip_stream);
+
+void smha_plan_destroy(smha_plan_t *plan); /* NULL is allowed */
+
+const char *smha_status_string(smha_status_t status);
+
+/* Name and average duration bookkeeping is left to the caller; this returns the symbol
+ * name of the kernel smha_forward would launch, for matching profiler output. */
+const char *smha_kernel_name(const smha_plan_t *plan, int d, smha_dtype_t in_dtype,
+                             smha_kernel_t kernel);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMHA_H */

@@ -1,0 +1,260 @@
+"""ctypes binding of include/smha.h: argument marshalling only.
+
+Function names mirror the C ABI.  torch is used for device memory and streams;
+numpy for host index arrays.  Nothing here computes attention.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+SMHA_F16, SMHA_BF16, SMHA_F32 = 0, 1, 2
+SMHA_KERNEL_AUTO, SMHA_KERNEL_ROW, SMHA_KERNEL_BLOCK = 0, 1, 2
+SMHA_SELECTOR_CALIBRATED, SMHA_SELECTOR_PAPER_EQ1 = 0, 1
+
+EXPORTS = {
+    "row_ptr": (0, np.int32), "col_idx": (1, np.int32),
+    "load_row_ptr": (2, np.int32), "load_col_idx": (3, np.int32),
+    "flags": (4, np.uint8), "bitmap": (5, np.uint64),
+    "full_row_ptr": (6, np.int32), "full_col_idx": (7, np.int32),
+    "part_row_ptr": (8, np.int32), "part_col_idx": (9, np.int32),
+    "bitmap_it8": (10, np.uint64),
+}
+
+
+class SmhaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {smha_status_string(status)} (status {status})")
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("block", C.c_int), ("force", C.c_int), ("selector", C.c_int),
+                ("build_both", C.c_int), ("device_id", C.c_int), ("head_dim", C.c_int)]
+
+
+class MaskDesc(C.Structure):
+    _fields_ = [("flags", C.c_uint32), ("window_left", C.c_int), ("window_right", C.c_int),
+                ("n_global", C.c_int), ("stride", C.c_int), ("stride_phase", C.c_int),
+                ("block", C.c_int), ("keep_p", C.c_double), ("n_window_blocks", C.c_int),
+                ("n_global_blocks", C.c_int), ("n_random_blocks", C.c_int), ("seed", C.c_uint64),
+                ("per_head", C.c_int), ("valid_len", C.POINTER(C.c_int32))]
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [("S", C.c_int), ("Bm", C.c_int), ("Hm", C.c_int), ("block", C.c_int),
+                ("kernel", C.c_int), ("has_row_format", C.c_int),
+                ("has_block_kernel_lists", C.c_int), ("on_device", C.c_int),
+                ("nnz", C.c_int64), ("n_valid", C.c_int64), ("n_full", C.c_int64),
+                ("n_part", C.c_int64), ("n_valid16", C.c_int64), ("n_tiles64", C.c_int64),
+                ("n_items", C.c_int64), ("n_split_rows", C.c_int64),
+                ("eq1_threshold", C.c_double), ("model_row_us", C.c_double),
+                ("model_block_us", C.c_double)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library(force=True)  # raises if hipcc is missing or the build fails
+    lib = C.CDLL(_build.LIB)
+    vp = C.c_void_p
+    lib.smha_plan_from_dense.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int,
+                                         C.POINTER(PlanOpts), C.POINTER(vp)]
+    lib.smha_plan_from_dense.restype = C.c_int
+    lib.smha_plan_from_desc.argtypes = [C.POINTER(MaskDesc), C.c_int, C.c_int, C.c_int,
+                                        C.POINTER(PlanOpts), C.POINTER(vp)]
+    lib.smha_plan_from_desc.restype = C.c_int
+    lib.smha_plan_info.argtypes = [vp, C.POINTER(PlanInfo)]
+    lib.smha_plan_info.restype = C.c_int
+    lib.smha_plan_export.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.smha_plan_export.restype = C.c_int
+    lib.smha_forward.argtypes = [vp, vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                 C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                 C.POINTER(C.c_int64), C.c_float, C.c_int, vp]
+    lib.smha_forward.restype = C.c_int
+    lib.smha_plan_destroy.argtypes = [vp]
+    lib.smha_plan_destroy.restype = None
+    lib.smha_status_string.argtypes = [C.c_int]
+    lib.smha_status_string.restype = C.c_char_p
+    lib.smha_kernel_name.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.smha_kernel_name.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def smha_status_string(status: int) -> str:
+    return _load().smha_status_string(int(status)).decode()
+
+
+def _opts(block=0, force=SMHA_KERNEL_AUTO, selector=SMHA_SELECTOR_CALIBRATED, build_both=False,
+          device_id=-1, head_dim=0) -> PlanOpts:
+    return PlanOpts(int(block), int(force), int(selector), int(bool(build_both)), int(device_id),
+                    int(head_dim))
+
+
+def smha_plan_from_dense(mask, **opts) -> int:
+    """mask: numpy uint8 [Bm,Hm,S,S] (host) or a torch uint8/bool CUDA tensor (device).
+    Returns the plan handle (an integer address)."""
+    lib = _load()
+    if isinstance(mask, np.ndarray):
+        if mask.dtype != np.uint8 or mask.ndim != 4 or mask.shape[2] != mask.shape[3]:
+            raise ValueError("mask must be uint8 [Bm,Hm,S,S]")
+        m = np.ascontiguousarray(mask)
+        ptr, on_dev = m.ctypes.data, 0
+    else:  # torch tensor on the GPU
+        if mask.ndim != 4 or mask.shape[2] != mask.shape[3] or mask.element_size() != 1:
+            raise ValueError("mask must be a 1-byte [Bm,Hm,S,S] tensor")
+        m = mask.contiguous()
+        ptr, on_dev = m.data_ptr(), (1 if m.is_cuda else 0)
+    Bm, Hm, S, _ = m.shape
+    out = C.c_void_p()
+    o = _opts(**opts)
+    st = lib.smha_plan_from_dense(C.c_void_p(ptr), on_dev, Bm, Hm, S, C.byref(o), C.byref(out))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_from_dense")
+    return out.value
+
+
+def smha_plan_from_desc(spec, B: int, H: int, S: int, **opts) -> int:
+    """spec: any object with the fields of smha_mask_desc_t (e.g. workloads.MaskSpec)."""
+    lib = _load()
+    vl = getattr(spec, "valid_len", None)
+    arr = None
+    d = MaskDesc(int(spec.flags), int(spec.window_left), int(spec.window_right), int(spec.n_global),
+                 int(spec.stride), int(spec.stride_phase), int(spec.block), float(spec.keep_p),
+                 int(spec.n_window_blocks), int(spec.n_global_blocks), int(spec.n_random_blocks),
+                 int(spec.seed), int(bool(spec.per_head)), None)
+    if vl is not None:
+        arr = (C.c_int32 * len(vl))(*[int(v) for v in vl])
+        d.valid_len = C.cast(arr, C.POINTER(C.c_int32))
+    out = C.c_void_p()
+    o = _opts(**opts)
+    st = lib.smha_plan_from_desc(C.byref(d), B, H, S, C.byref(o), C.byref(out))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_from_desc")
+    return out.value
+
+
+def smha_plan_info(plan: int) -> dict:
+    info = PlanInfo()
+    st = _load().smha_plan_info(C.c_void_p(plan), C.byref(info))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_info")
+    return {name: getattr(info, name) for name, _ in PlanInfo._fields_}
+
+
+def smha_plan_export(plan: int, which: str, mask_index: int = 0) -> np.ndarray:
+    code, dtype = EXPORTS[which]
+    lib = _load()
+    need = C.c_size_t(0)
+    st = lib.smha_plan_export(C.c_void_p(plan), mask_index, code, None, 0, C.byref(need))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_export")
+    out = np.empty(need.value // np.dtype(dtype).itemsize, dtype=dtype)
+    if need.value:
+        st = lib.smha_plan_export(C.c_void_p(plan), mask_index, code, C.c_void_p(out.ctypes.data),
+                                  need.value, C.byref(need))
+        if st != 0:
+            raise SmhaError(st, "smha_plan_export")
+    return out
+
+
+def smha_plan_destroy(plan: Optional[int]) -> None:
+    if plan:
+        _load().smha_plan_destroy(C.c_void_p(plan))
+
+
+def smha_kernel_name(plan: int, d: int, in_dtype: int, kernel: int = SMHA_KERNEL_AUTO) -> str:
+    return _load().smha_kernel_name(C.c_void_p(plan), d, in_dtype, kernel).decode()
+
+
+def _strides3(t):
+    st = t.stride()
+    if st[3] != 1:
+        raise ValueError("head_dim must be contiguous")
+    return (C.c_int64 * 3)(st[0], st[1], st[2])
+
+
+def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
+                 stream=None) -> None:
+    """Q, K, V, O: torch CUDA tensors [B,H,S,d]; O in the input dtype or float32.
+    Enqueues on `stream` (default: torch's current stream); does not synchronise."""
+    import torch
+    B, H, S, d = Q.shape
+    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape:
+        raise ValueError("Q, K, V, O must share one [B,H,S,d] shape")
+    codes = {torch.float16: SMHA_F16, torch.bfloat16: SMHA_BF16, torch.float32: SMHA_F32}
+    if Q.dtype not in (torch.float16, torch.bfloat16) or K.dtype != Q.dtype or V.dtype != Q.dtype:
+        raise ValueError("Q, K, V must be float16 or bfloat16")
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda and O.is_cuda):
+        raise ValueError("tensors must be on the GPU")
+    if stream is None:
+        stream = torch.cuda.current_stream(Q.device)
+    handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    st = _load().smha_forward(C.c_void_p(plan), C.c_void_p(Q.data_ptr()), C.c_void_p(K.data_ptr()),
+                              C.c_void_p(V.data_ptr()), C.c_void_p(O.data_ptr()), B, H, d,
+                              codes[Q.dtype], codes[O.dtype], _strides3(Q), _strides3(K),
+                              _strides3(V), _strides3(O), float(scale), int(kernel),
+                              C.c_void_p(handle))
+    if st != 0:
+        raise SmhaError(st, "smha_forward")
+
+
+class Plan:
+    """Owns one smha_plan_t handle."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    @classmethod
+    def from_dense(cls, mask, **opts) -> "Plan":
+        return cls(smha_plan_from_dense(mask, **opts))
+
+    @classmethod
+    def from_desc(cls, spec, B: int, H: int, S: int, **opts) -> "Plan":
+        return cls(smha_plan_from_desc(spec, B, H, S, **opts))
+
+    def info(self) -> dict:
+        return smha_plan_info(self.handle)
+
+    def export(self, which: str, mask_index: int = 0) -> np.ndarray:
+        return smha_plan_export(self.handle, which, mask_index)
+
+    def forward(self, Q, K, V, out=None, out_dtype=None, scale: float = 0.0,
+                kernel: int = SMHA_KERNEL_AUTO, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty(Q.shape, dtype=out_dtype or Q.dtype, device=Q.device)
+        smha_forward(self.handle, Q, K, V, out, scale, kernel, stream)
+        return out
+
+    def close(self) -> None:
+        if self.handle:
+            smha_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

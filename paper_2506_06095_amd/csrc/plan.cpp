@@ -1,0 +1,669 @@
+// Host-side mask analysis: dense mask or pattern description -> per-row format, two-level
+// block format (Sec. 4.2.1 of the paper), kernel selection (Sec. 4.2.3) and the block
+// kernel's work lists.  Integer work only; runs without a GPU.
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <thread>
+
+#include "smha_internal.hpp"
+
+namespace smha {
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Row sources: produce one mask row as a bit string (bit j of word j/64 = entry (i, j)).
+// ---------------------------------------------------------------------------------------
+struct RowSource {
+    virtual ~RowSource() = default;
+    virtual void row_bits(int i, uint64_t *words) const = 0;  // words[W], W = ceil(S/64)
+};
+
+inline void set_range(uint64_t *w, int lo, int hi) {  // bits [lo, hi)
+    if (lo >= hi) return;
+    int wl = lo >> 6, wh = (hi - 1) >> 6;
+    uint64_t ml = ~0ull << (lo & 63);
+    uint64_t mh = ~0ull >> (63 - ((hi - 1) & 63));
+    if (wl == wh) {
+        w[wl] |= ml & mh;
+        return;
+    }
+    w[wl] |= ml;
+    for (int t = wl + 1; t < wh; ++t) w[t] = ~0ull;
+    w[wh] |= mh;
+}
+
+inline void keep_below(uint64_t *w, int W, int n) {  // clear bits >= n
+    int full = n >> 6;
+    if (full < W) {
+        int rem = n & 63;
+        if (rem) {
+            w[full] &= ~0ull >> (64 - rem);
+            ++full;
+        }
+        for (int t = full; t < W; ++t) w[t] = 0;
+    }
+}
+
+struct DenseSource final : RowSource {
+    const uint8_t *m;
+    int S, W;
+    DenseSource(const uint8_t *mask, int S_) : m(mask), S(S_), W((S_ + 63) / 64) {}
+    void row_bits(int i, uint64_t *words) const override {
+        const uint8_t *r = m + (size_t)i * S;
+        int j = 0;
+        for (int t = 0; t < W; ++t) {
+            uint64_t out = 0;
+            for (int byte = 0; byte < 8 && j < S; ++byte) {
+                if (j + 8 <= S) {
+                    uint64_t x;
+                    std::memcpy(&x, r + j, 8);
+                    // any nonzero byte -> its bit 0, then gather the eight bit-0s
+                    x |= x >> 4;
+                    x |= x >> 2;
+                    x |= x >> 1;
+                    x &= 0x0101010101010101ull;
+                    out |= ((x * 0x0102040810204080ull) >> 56) << (8 * byte);
+                    j += 8;
+                } else {
+                    for (int b = 0; j < S; ++b, ++j)
+                        if (r[j]) out |= 1ull << (8 * byte + b);
+                }
+            }
+            words[t] = out;
+        }
+    }
+};
+
+inline uint64_t mix64(uint64_t x) {  // splitmix64 output function
+    x += 0x9E3779B97F4A7C15ull;
+    uint64_t z = x;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+inline uint64_t block_hash(uint64_t seed, uint64_t head, uint32_t br, uint32_t bc) {
+    uint64_t key = mix64(seed ^ mix64(head));
+    return mix64(key ^ (((uint64_t)br << 32) | bc));
+}
+
+struct DescSource final : RowSource {
+    smha_mask_desc_t d;
+    int S, W, valid;
+    std::vector<std::vector<int32_t>> keep;  // per block row of d.block: kept block columns
+    DescSource(const smha_mask_desc_t &desc, int S_, int head, int valid_)
+        : d(desc), S(S_), W((S_ + 63) / 64), valid(valid_) {
+        if (!(d.flags & (SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD))) return;
+        const int bs = d.block, nb = (S + bs - 1) / bs;
+        keep.resize(nb);
+        std::vector<uint8_t> row(nb);
+        std::vector<std::pair<uint64_t, int32_t>> cand;
+        for (int br = 0; br < nb; ++br) {
+            std::fill(row.begin(), row.end(), 0);
+            if (d.flags & SMHA_MASK_BLOCK_RANDOM) {
+                for (int bc = 0; bc < nb; ++bc) {
+                    double u = (double)(block_hash(d.seed, head, br, bc) >> 11) *
+                               (1.0 / 9007199254740992.0);
+                    if (bc == br || u < d.keep_p) row[bc] = 1;
+                }
+            }
+            if (d.flags & SMHA_MASK_BIGBIRD) {
+                std::vector<uint8_t> bb(nb, 0);
+                const int half = (d.n_window_blocks - 1) / 2;
+                if (d.n_window_blocks > 0)
+                    for (int bc = std::max(0, br - half); bc < std::min(nb, br + half + 1); ++bc)
+                        bb[bc] = 1;
+                for (int bc = 0; bc < std::min(nb, d.n_global_blocks); ++bc) bb[bc] = 1;
+                if (br < d.n_global_blocks) std::fill(bb.begin(), bb.end(), 1);
+                cand.clear();
+                for (int bc = 0; bc < nb; ++bc)
+                    if (!bb[bc]) cand.emplace_back(block_hash(d.seed, head, br, bc), bc);
+                std::sort(cand.begin(), cand.end());
+                for (int t = 0; t < (int)cand.size() && t < d.n_random_blocks; ++t)
+                    bb[cand[t].second] = 1;
+                for (int bc = 0; bc < nb; ++bc) row[bc] |= bb[bc];
+            }
+            for (int bc = 0; bc < nb; ++bc)
+                if (row[bc]) keep[br].push_back(bc);
+        }
+    }
+    void row_bits(int i, uint64_t *w) const override {
+        std::memset(w, 0, sizeof(uint64_t) * W);
+        const uint32_t f = d.flags;
+        const uint32_t additive = f & (SMHA_MASK_WINDOW | SMHA_MASK_GLOBAL | SMHA_MASK_STRIDED |
+                                       SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD);
+        if (!additive) set_range(w, 0, S);
+        if (f & SMHA_MASK_WINDOW) {
+            int64_t lo = (int64_t)i - d.window_left, hi = (int64_t)i + d.window_right + 1;
+            set_range(w, (int)std::max<int64_t>(0, lo), (int)std::min<int64_t>(S, hi));
+        }
+        if (f & SMHA_MASK_GLOBAL) set_range(w, 0, i < d.n_global ? S : std::min(S, d.n_global));
+        if (f & SMHA_MASK_STRIDED)
+            for (int j = d.stride_phase; j < S; j += d.stride) w[j >> 6] |= 1ull << (j & 63);
+        if (!keep.empty()) {
+            const int bs = d.block;
+            for (int32_t bc : keep[i / bs])
+                set_range(w, bc * bs, std::min<int64_t>(S, (int64_t)(bc + 1) * bs));
+        }
+        if (f & SMHA_MASK_CAUSAL) keep_below(w, W, i + 1);
+        if (f & SMHA_MASK_PADDING) keep_below(w, W, i < valid ? valid : 0);
+    }
+};
+
+// ---------------------------------------------------------------------------------------
+// One stripe = 64 consecutive mask rows.  Everything downstream is derived from its bits.
+// ---------------------------------------------------------------------------------------
+struct Stripe {
+    int32_t row_nnz[64];
+    std::vector<int32_t> cols;                // per-row format, rows concatenated
+    std::vector<int32_t> load_col[4];         // per block row inside the stripe (64/block of them)
+    std::vector<uint8_t> flag[4];
+    std::vector<uint64_t> bitmap[4];
+    std::vector<int32_t> kt_col, kt_bmp_local;  // 64x64 tiles (only when block != 64)
+    std::vector<uint64_t> kt_bitmap;
+    int64_t valid16 = 0, nnz = 0;
+};
+
+inline uint64_t extract_bits(const uint64_t *row, int c0, int n) {  // n <= 64, c0 % n == 0
+    uint64_t w = row[c0 >> 6] >> (c0 & 63);
+    return n == 64 ? w : (w & ((1ull << n) - 1));
+}
+
+void analyse_stripe(const RowSource &src, int S, int block, bool want_rows, int stripe,
+                    uint64_t *bits /* 64*W */, Stripe &out) {
+    const int W = (S + 63) / 64;
+    const int r0 = stripe * 64;
+    for (int r = 0; r < 64; ++r) {
+        uint64_t *w = bits + (size_t)r * W;
+        if (r0 + r < S)
+            src.row_bits(r0 + r, w);
+        else
+            std::memset(w, 0, sizeof(uint64_t) * W);
+        int c = 0;
+        for (int t = 0; t < W; ++t) c += __builtin_popcountll(w[t]);
+        out.row_nnz[r] = c;
+        out.nnz += c;
+    }
+    if (want_rows) {
+        out.cols.reserve(out.nnz);
+        for (int r = 0; r < 64; ++r) {
+            const uint64_t *w = bits + (size_t)r * W;
+            for (int t = 0; t < W; ++t) {
+                uint64_t x = w[t];
+                while (x) {
+                    out.cols.push_back(t * 64 + __builtin_ctzll(x));
+                    x &= x - 1;
+                }
+            }
+        }
+    }
+    // non-empty 16x16 tiles (input of the paper's Eq. 1)
+    for (int g = 0; g < 4; ++g) {
+        if (r0 + g * 16 >= S) break;
+        for (int t = 0; t < W; ++t) {
+            uint64_t any = 0;
+            for (int r = 0; r < 16; ++r) any |= bits[(size_t)(g * 16 + r) * W + t];
+            for (int q = 0; q < 4; ++q)
+                if ((any >> (16 * q)) & 0xFFFF) ++out.valid16;
+        }
+    }
+    // tiles of edge `block`
+    const int nb = (S + block - 1) / block;
+    const int per = 64 / block;
+    for (int sub = 0; sub < per; ++sub) {
+        if (r0 + sub * block >= S) break;
+        for (int bc = 0; bc < nb; ++bc) {
+            uint64_t words[64];
+            int cnt = 0;
+            for (int r = 0; r < block; ++r) {
+                words[r] = extract_bits(bits + (size_t)(sub * block + r) * W, bc * block, block);
+                cnt += __builtin_popcountll(words[r]);
+            }
+            if (!cnt) continue;
+            out.load_col[sub].push_back(bc);
+            const bool full = cnt == block * block;
+            out.flag[sub].push_back(full ? 1 : 0);
+            if (!full) out.bitmap[sub].insert(out.bitmap[sub].end(), words, words + block);
+        }
+    }
+    if (block != 64) {
+        for (int kt = 0; kt < W; ++kt) {
+            uint64_t words[64];
+            int cnt = 0;
+            for (int r = 0; r < 64; ++r) {
+                words[r] = bits[(size_t)r * W + kt];
+                cnt += __builtin_popcountll(words[r]);
+            }
+            if (!cnt) continue;
+            out.kt_col.push_back(kt);
+            if (cnt == 64 * 64) {
+                out.kt_bmp_local.push_back(-1);
+            } else {
+                out.kt_bmp_local.push_back((int32_t)(out.kt_bitmap.size() / 64));
+                out.kt_bitmap.insert(out.kt_bitmap.end(), words, words + 64);
+            }
+        }
+    }
+}
+
+smha_status_t analyse_mask(const RowSource &src, int S, int block, bool want_rows,
+                           MaskFormats &mf) {
+    const int W = (S + 63) / 64;
+    const int n_stripes = (S + 63) / 64;
+    std::vector<Stripe> stripes(n_stripes);
+    std::atomic<int> next{0};
+    std::atomic<bool> failed{false};
+    int n_threads = (int)std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
+    n_threads = std::min(n_threads, n_stripes);
+    if ((int64_t)S * S < (1 << 20)) n_threads = 1;
+    auto work = [&]() {
+        try {
+            std::vector<uint64_t> bits((size_t)64 * W);
+            for (;;) {
+                int s = next.fetch_add(1);
+                if (s >= n_stripes) break;
+                analyse_stripe(src, S, block, want_rows, s, bits.data(), stripes[s]);
+            }
+        } catch (const std::bad_alloc &) {
+            failed = true;
+        }
+    };
+    if (n_threads <= 1) {
+        work();
+    } else {
+        std::vector<std::thread> pool;
+        for (int t = 0; t < n_threads; ++t) pool.emplace_back(work);
+        for (auto &t : pool) t.join();
+    }
+    if (failed) return SMHA_ERR_ALLOC;
+
+    const int nbr = (S + block - 1) / block;
+    const int per = 64 / block;
+    mf.load_row_ptr.assign(nbr + 1, 0);
+    mf.full_row_ptr.assign(nbr + 1, 0);
+    mf.part_row_ptr.assign(nbr + 1, 0);
+    if (want_rows) {
+        mf.row_ptr.assign(S + 1, 0);
+        int64_t total = 0;
+        for (auto &st : stripes) total += st.nnz;
+        if (total > INT32_MAX) return SMHA_ERR_UNSUPPORTED;
+        mf.col_idx.reserve(total);
+    }
+    mf.kt_row_ptr.assign(n_stripes + 1, 0);
+    for (int s = 0; s < n_stripes; ++s) {
+        Stripe &st = stripes[s];
+        mf.nnz += st.nnz;
+        mf.n_valid16 += st.valid16;
+        if (want_rows) {
+            for (int r = 0; r < 64 && s * 64 + r < S; ++r)
+                mf.row_ptr[s * 64 + r + 1] = mf.row_ptr[s * 64 + r] + st.row_nnz[r];
+            mf.col_idx.insert(mf.col_idx.end(), st.cols.begin(), st.cols.end());
+        }
+        for (int sub = 0; sub < per; ++sub) {
+            const int br = s * per + sub;
+            if (br >= nbr) break;
+            for (size_t e = 0; e < st.load_col[sub].size(); ++e) {
+                mf.load_col_idx.push_back(st.load_col[sub][e]);
+                mf.flags.push_back(st.flag[sub][e]);
+                (st.flag[sub][e] ? mf.full_col_idx : mf.part_col_idx).push_back(st.load_col[sub][e]);
+            }
+            mf.bitmap.insert(mf.bitmap.end(), st.bitmap[sub].begin(), st.bitmap[sub].end());
+            mf.load_row_ptr[br + 1] = (int32_t)mf.load_col_idx.size();
+            mf.full_row_ptr[br + 1] = (int32_t)mf.full_col_idx.size();
+            mf.part_row_ptr[br + 1] = (int32_t)mf.part_col_idx.size();
+        }
+        if (block != 64) {
+            const int32_t base = (int32_t)(mf.kt_bitmap.size() / 64);
+            for (size_t e = 0; e < st.kt_col.size(); ++e) {
+                mf.kt_col.push_back(st.kt_col[e]);
+                mf.kt_bmp.push_back(st.kt_bmp_local[e] < 0 ? -1 : base + st.kt_bmp_local[e]);
+            }
+            mf.kt_bitmap.insert(mf.kt_bitmap.end(), st.kt_bitmap.begin(), st.kt_bitmap.end());
+            mf.kt_row_ptr[s + 1] = (int32_t)mf.kt_col.size();
+        }
+        Stripe().cols.swap(st.cols);  // release early
+    }
+    if (block == 64) {  // the kernel's tiles ARE the exported tiles
+        mf.kt_row_ptr = mf.load_row_ptr;
+        mf.kt_col = mf.load_col_idx;
+        mf.kt_bmp.resize(mf.flags.size());
+        int32_t part = 0;
+        for (size_t e = 0; e < mf.flags.size(); ++e) mf.kt_bmp[e] = mf.flags[e] ? -1 : part++;
+        mf.kt_bitmap = mf.bitmap;
+    }
+    return SMHA_OK;
+}
+
+smha_status_t check_opts(const smha_plan_opts_t *in, smha_plan_opts_t &o) {
+    o = smha_plan_opts_t{};
+    if (in) o = *in;
+    if (o.block == 0) o.block = 64;
+    if (o.block != 16 && o.block != 32 && o.block != 64) return SMHA_ERR_UNSUPPORTED;
+    if (o.force < SMHA_KERNEL_AUTO || o.force > SMHA_KERNEL_BLOCK) return SMHA_ERR_INVALID_ARG;
+    if (o.selector != SMHA_SELECTOR_CALIBRATED && o.selector != SMHA_SELECTOR_PAPER_EQ1)
+        return SMHA_ERR_INVALID_ARG;
+    if (o.device_id < -2) return SMHA_ERR_INVALID_ARG;
+    if (o.head_dim == 0) o.head_dim = 64;
+    if (o.head_dim != 64 && o.head_dim != 128) return SMHA_ERR_UNSUPPORTED;
+    return SMHA_OK;
+}
+
+// The selector needs tile statistics, so both formats are always *analysed*; the per-row
+// column list is the only large array and is kept only when it can be used.
+bool rows_wanted(const smha_plan_opts_t &o) {
+    return true;  // decided after analysis; see finish_plan (drops col_idx if unused)
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------
+// Kernel selection (Sec. 4.2.3).
+//   paper:      threshold = valid16 / n^2 - tau / (log2 n)^2, n = ceil(S/16), tau = 1.2;
+//               row-wise iff threshold < 0 (n == 1: row-wise).
+//   calibrated: compare modelled times per (batch, head) pair:
+//               block = tiles64 * t_tile(d) ; row = nnz * t_entry(d) + S * t_rowfix
+// ---------------------------------------------------------------------------------------
+static double eq1_threshold(double valid16, int S) {
+    const double n = std::ceil(S / 16.0);
+    if (n <= 1.0) return -INFINITY;
+    const double lg = std::log2(n);
+    return valid16 / (n * n) - 1.2 / (lg * lg);
+}
+
+// Cost-model constants in nanoseconds, per (batch, head) pair on a busy MI355X.
+struct CostModel {
+    double tile_ns, entry_ns, row_ns;
+};
+static CostModel cost_model(int d) {
+    // t_tile: one 64x64 tile of the block kernel; t_entry: one unmasked entry of the row
+    // kernel (a K row and a V row gathered through L2); t_row: fixed cost per query row.
+    if (d == 128) return {0.70, 0.014, 0.020};
+    return {0.45, 0.008, 0.015};
+}
+
+smha_status_t finish_plan(smha_plan *p) {
+    const int n_masks = p->Bm * p->Hm;
+    const int S = p->S;
+    double v16 = 0, nnz = 0, tiles = 0;
+    for (auto &m : p->masks) {
+        v16 += (double)m.n_valid16;
+        nnz += (double)m.nnz;
+        tiles += (double)m.kt_col.size();
+    }
+    v16 /= n_masks;
+    nnz /= n_masks;
+    tiles /= n_masks;
+    p->eq1_threshold = eq1_threshold(v16, S);
+    const CostModel cm = cost_model(p->opts.head_dim);
+    p->model_block_us = 1e-3 * (tiles * cm.tile_ns);
+    p->model_row_us = 1e-3 * (nnz * cm.entry_ns + S * cm.row_ns);
+
+    int choice;
+    if (p->opts.force != SMHA_KERNEL_AUTO)
+        choice = p->opts.force;
+    else if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1)
+        choice = p->eq1_threshold < 0 ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
+    else
+        choice = p->model_row_us < p->model_block_us ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
+    p->kernel = choice;
+    p->has_row = p->opts.build_both || choice == SMHA_KERNEL_ROW;
+    p->has_block = p->opts.build_both || choice == SMHA_KERNEL_BLOCK;
+
+    try {
+        // ---- row path: concatenate -------------------------------------------------
+        if (p->has_row) {
+            p->h_row_ptr.reserve((size_t)n_masks * (S + 1));
+            int64_t off = 0;
+            for (auto &m : p->masks) {
+                p->h_col_off.push_back(off);
+                p->h_row_ptr.insert(p->h_row_ptr.end(), m.row_ptr.begin(), m.row_ptr.end());
+                off += (int64_t)m.col_idx.size();
+            }
+            p->h_col_idx.reserve(off);
+            for (auto &m : p->masks)
+                p->h_col_idx.insert(p->h_col_idx.end(), m.col_idx.begin(), m.col_idx.end());
+        }
+        // ---- block path: tiles, work items, split rows ---------------------------
+        if (p->has_block) {
+            const int nqt = (S + kTile - 1) / kTile;
+            for (int mi = 0; mi < n_masks; ++mi) {
+                MaskFormats &m = p->masks[mi];
+                const int32_t tile_base = (int32_t)p->h_kt_col.size();
+                const int32_t bmp_base = (int32_t)(p->h_kt_bitmap.size() / 64);
+                p->h_kt_col.insert(p->h_kt_col.end(), m.kt_col.begin(), m.kt_col.end());
+                for (int32_t b : m.kt_bmp) p->h_kt_bmp.push_back(b < 0 ? -1 : b + bmp_base);
+                p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), m.kt_bitmap.begin(), m.kt_bitmap.end());
+
+                // split query tiles whose tile list is much longer than the typical one, so
+                // that a few heavy rows (global tokens) do not serialise on one workgroup
+                int64_t n_nonempty = 0;
+                for (int q = 0; q < nqt; ++q) n_nonempty += m.kt_row_ptr[q + 1] > m.kt_row_ptr[q];
+                const double avg = n_nonempty ? (double)m.kt_col.size() / n_nonempty : 0.0;
+                const int chunk = std::max(16, (int)std::ceil(2.0 * avg));
+                std::vector<Item> items;
+                std::vector<SplitRow> splits;
+                int32_t slots = 0;
+                for (int q = 0; q < nqt; ++q) {
+                    const int32_t b = tile_base + m.kt_row_ptr[q], e = tile_base + m.kt_row_ptr[q + 1];
+                    const int n = e - b;
+                    if (n <= chunk) {
+                        items.push_back({q, b, e, -1});
+                        continue;
+                    }
+                    const int parts = (n + chunk - 1) / chunk;
+                    splits.push_back({q, slots, parts, 0});
+                    for (int c = 0; c < parts; ++c) {
+                        const int32_t cb = b + (int32_t)((int64_t)n * c / parts);
+                        const int32_t ce = b + (int32_t)((int64_t)n * (c + 1) / parts);
+                        items.push_back({q, cb, ce, slots++});
+                    }
+                }
+                std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
+                    return (a.end - a.begin) > (b.end - b.begin);
+                });
+                p->h_item_off.push_back((int32_t)p->h_items.size());
+                p->h_item_cnt.push_back((int32_t)items.size());
+                p->h_items.insert(p->h_items.end(), items.begin(), items.end());
+                p->h_split_off.push_back((int32_t)p->h_split_rows.size());
+                p->h_split_cnt.push_back((int32_t)splits.size());
+                p->h_split_rows.insert(p->h_split_rows.end(), splits.begin(), splits.end());
+                p->max_items = std::max(p->max_items, (int)items.size());
+                p->max_split_rows = std::max(p->max_split_rows, (int)splits.size());
+                p->max_slots = std::max(p->max_slots, (int)slots);
+            }
+        }
+        // the per-row column list is large; drop it when no kernel will read it
+        if (!p->has_row)
+            for (auto &m : p->masks) {
+                // keep row_ptr/col_idx for export only when explicitly requested (build_both)
+                std::vector<int32_t>().swap(m.col_idx);
+                std::vector<int32_t>().swap(m.row_ptr);
+            }
+    } catch (const std::bad_alloc &) {
+        return SMHA_ERR_ALLOC;
+    }
+
+    int dev = p->opts.device_id;
+    if (dev == -2) return SMHA_OK;
+    if (dev == -1) {
+        dev = current_device_or_negative();
+        if (dev < 0) return SMHA_OK;  // host-only plan; forward will report SMHA_ERR_HIP
+    }
+    return upload_plan(p, dev);
+}
+
+}  // namespace smha
+
+using namespace smha;
+
+extern "C" smha_status_t smha_plan_from_dense(const uint8_t *mask, int mask_on_device, int Bm,
+                                              int Hm, int S, const smha_plan_opts_t *opts,
+                                              smha_plan_t **out) {
+    if (!mask || !out || Bm < 1 || Hm < 1 || S < 1) return SMHA_ERR_INVALID_ARG;
+    smha_plan_opts_t o;
+    smha_status_t st = check_opts(opts, o);
+    if (st != SMHA_OK) return st;
+    try {
+        std::unique_ptr<smha_plan> p(new smha_plan);
+        p->S = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
+        const size_t per_mask = (size_t)S * S;
+        std::vector<uint8_t> staged;
+        const uint8_t *host = mask;
+        if (mask_on_device) {
+            staged.resize(per_mask * Bm * Hm);
+            st = copy_mask_to_host(mask, staged.size(), staged.data());
+            if (st != SMHA_OK) return st;
+            host = staged.data();
+        }
+        p->masks.resize((size_t)Bm * Hm);
+        for (int mi = 0; mi < Bm * Hm; ++mi) {
+            DenseSource src(host + per_mask * mi, S);
+            st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+            if (st != SMHA_OK) return st;
+        }
+        st = finish_plan(p.get());
+        if (st != SMHA_OK) { release_device(p.get()); return st; }
+        *out = p.release();
+        return SMHA_OK;
+    } catch (const std::bad_alloc &) {
+        return SMHA_ERR_ALLOC;
+    }
+}
+
+extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B, int H, int S,
+                                             const smha_plan_opts_t *opts, smha_plan_t **out) {
+    if (!desc || !out || B < 1 || H < 1 || S < 1) return SMHA_ERR_INVALID_ARG;
+    const smha_mask_desc_t &d = *desc;
+    const uint32_t known = SMHA_MASK_CAUSAL | SMHA_MASK_WINDOW | SMHA_MASK_GLOBAL | SMHA_MASK_STRIDED |
+                           SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD | SMHA_MASK_PADDING;
+    if (d.flags & ~known) return SMHA_ERR_INVALID_ARG;
+    if ((d.flags & SMHA_MASK_WINDOW) && (d.window_left < 0 || d.window_right < 0)) return SMHA_ERR_INVALID_ARG;
+    if ((d.flags & SMHA_MASK_GLOBAL) && d.n_global < 0) return SMHA_ERR_INVALID_ARG;
+    if ((d.flags & SMHA_MASK_STRIDED) && (d.stride < 1 || d.stride_phase < 0 || d.stride_phase >= d.stride))
+        return SMHA_ERR_INVALID_ARG;
+    if (d.flags & (SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD)) {
+        if (d.block < 1) return SMHA_ERR_INVALID_ARG;
+        if ((d.flags & SMHA_MASK_BLOCK_RANDOM) && !(d.keep_p >= 0.0 && d.keep_p <= 1.0)) return SMHA_ERR_INVALID_ARG;
+        if ((d.flags & SMHA_MASK_BIGBIRD) &&
+            (d.n_window_blocks < 0 || d.n_global_blocks < 0 || d.n_random_blocks < 0))
+            return SMHA_ERR_INVALID_ARG;
+    }
+    if (d.flags & SMHA_MASK_PADDING) {
+        if (!d.valid_len) return SMHA_ERR_INVALID_ARG;
+        for (int b = 0; b < B; ++b)
+            if (d.valid_len[b] < 0 || d.valid_len[b] > S) return SMHA_ERR_INVALID_ARG;
+    }
+    smha_plan_opts_t o;
+    smha_status_t st = check_opts(opts, o);
+    if (st != SMHA_OK) return st;
+    try {
+        std::unique_ptr<smha_plan> p(new smha_plan);
+        const int Bm = (d.flags & SMHA_MASK_PADDING) ? B : 1;
+        const int Hm = (d.per_head && (d.flags & (SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD))) ? H : 1;
+        p->S = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
+        p->masks.resize((size_t)Bm * Hm);
+        for (int b = 0; b < Bm; ++b)
+            for (int h = 0; h < Hm; ++h) {
+                const int valid = (d.flags & SMHA_MASK_PADDING) ? d.valid_len[b] : S;
+                DescSource src(d, S, h, valid);
+                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[(size_t)b * Hm + h]);
+                if (st != SMHA_OK) return st;
+            }
+        st = finish_plan(p.get());
+        if (st != SMHA_OK) { release_device(p.get()); return st; }
+        *out = p.release();
+        return SMHA_OK;
+    } catch (const std::bad_alloc &) {
+        return SMHA_ERR_ALLOC;
+    }
+}
+
+extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *out) {
+    if (!p || !out) return SMHA_ERR_INVALID_ARG;
+    smha_plan_info_t i{};
+    i.S = p->S; i.Bm = p->Bm; i.Hm = p->Hm; i.block = p->block; i.kernel = p->kernel;
+    i.has_row_format = p->has_row; i.has_block_kernel_lists = p->has_block; i.on_device = p->device >= 0;
+    for (auto &m : p->masks) {
+        i.nnz += m.nnz;
+        i.n_valid += (int64_t)m.load_col_idx.size();
+        i.n_full += (int64_t)m.full_col_idx.size();
+        i.n_part += (int64_t)m.part_col_idx.size();
+        i.n_valid16 += m.n_valid16;
+        i.n_tiles64 += (int64_t)m.kt_col.size();
+    }
+    i.n_items = (int64_t)p->h_items.size();
+    i.n_split_rows = (int64_t)p->h_split_rows.size();
+    i.eq1_threshold = p->eq1_threshold;
+    i.model_row_us = p->model_row_us;
+    i.model_block_us = p->model_block_us;
+    *out = i;
+    return SMHA_OK;
+}
+
+extern "C" smha_status_t smha_plan_export(const smha_plan_t *p, int mask_index, smha_export_t which,
+                                          void *host_dst, size_t cap, size_t *need) {
+    if (!p || !need || mask_index < 0 || mask_index >= p->Bm * p->Hm) return SMHA_ERR_INVALID_ARG;
+    if (cap > 0 && !host_dst) return SMHA_ERR_INVALID_ARG;
+    const MaskFormats &m = p->masks[mask_index];
+    const void *src = nullptr;
+    size_t bytes = 0;
+    std::vector<uint64_t> it8;
+    auto vec = [&](const auto &v) { src = v.data(); bytes = v.size() * sizeof(v[0]); };
+    switch (which) {
+        case SMHA_EXPORT_ROW_PTR:
+            if (m.row_ptr.empty()) return SMHA_ERR_UNSUPPORTED;
+            vec(m.row_ptr); break;
+        case SMHA_EXPORT_COL_IDX:
+            if (m.row_ptr.empty()) return SMHA_ERR_UNSUPPORTED;
+            vec(m.col_idx); break;
+        case SMHA_EXPORT_LOAD_ROW_PTR: vec(m.load_row_ptr); break;
+        case SMHA_EXPORT_LOAD_COL_IDX: vec(m.load_col_idx); break;
+        case SMHA_EXPORT_BLOCK_FLAGS: vec(m.flags); break;
+        case SMHA_EXPORT_BITMAP: vec(m.bitmap); break;
+        case SMHA_EXPORT_FULL_ROW_PTR: vec(m.full_row_ptr); break;
+        case SMHA_EXPORT_FULL_COL_IDX: vec(m.full_col_idx); break;
+        case SMHA_EXPORT_PART_ROW_PTR: vec(m.part_row_ptr); break;
+        case SMHA_EXPORT_PART_COL_IDX: vec(m.part_col_idx); break;
+        case SMHA_EXPORT_BITMAP_IT8: {
+            if (p->block != 64) return SMHA_ERR_UNSUPPORTED;
+            const size_t np = m.bitmap.size() / 64;
+            try { it8.assign(np * 64, 0); } catch (const std::bad_alloc &) { return SMHA_ERR_ALLOC; }
+            for (size_t t = 0; t < np; ++t)
+                for (int ir = 0; ir < 8; ++ir)
+                    for (int ic = 0; ic < 8; ++ic) {
+                        uint64_t w = 0;
+                        for (int r = 0; r < 8; ++r)
+                            w |= ((m.bitmap[t * 64 + ir * 8 + r] >> (8 * ic)) & 0xFFull) << (8 * r);
+                        it8[t * 64 + ic * 8 + ir] = w;
+                    }
+            vec(it8);
+            break;
+        }
+        default: return SMHA_ERR_INVALID_ARG;
+    }
+    *need = bytes;
+    if (cap >= bytes && bytes) std::memcpy(host_dst, src, bytes);
+    return SMHA_OK;
+}
+
+extern "C" void smha_plan_destroy(smha_plan_t *p) {
+    if (!p) return;
+    release_device(p);
+    delete p;
+}
+
+extern "C" const char *smha_status_string(smha_status_t s) {
+    switch (s) {
+        case SMHA_OK: return "ok";
+        case SMHA_ERR_INVALID_ARG: return "invalid argument";
+        case SMHA_ERR_UNSUPPORTED: return "unsupported configuration";
+        case SMHA_ERR_SHAPE: return "shape mismatch";
+        case SMHA_ERR_ALLOC: return "allocation failed";
+        case SMHA_ERR_HIP: return "HIP error or no usable GPU";
+    }
+    return "unknown status";
+}

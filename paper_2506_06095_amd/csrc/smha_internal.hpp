@@ -1,0 +1,95 @@
+// Internal definitions shared by the host planner and the HIP launch code.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "smha.h"
+
+namespace smha {
+
+constexpr int kTile = 64;  // query rows per work item and keys per K/V tile of the block kernel
+
+// Formats of one distinct mask (Sec. 4.2.1 of the paper for the block arrays).
+struct MaskFormats {
+    int64_t nnz = 0;
+    int64_t n_valid16 = 0;
+    std::vector<int32_t> row_ptr, col_idx;                 // per-row format (optional)
+    std::vector<int32_t> load_row_ptr, load_col_idx;       // all non-empty tiles
+    std::vector<int32_t> full_row_ptr, full_col_idx;       // completely unmasked tiles
+    std::vector<int32_t> part_row_ptr, part_col_idx;       // partially masked tiles
+    std::vector<uint8_t> flags;                            // per load entry, 1 = full
+    std::vector<uint64_t> bitmap;                          // n_part * block words
+    // 64x64 tiles visited by the block kernel (identical to the arrays above when block == 64)
+    std::vector<int32_t> kt_row_ptr, kt_col, kt_bmp;       // kt_bmp: bitmap index or -1 (full)
+    std::vector<uint64_t> kt_bitmap;                       // n_part64 * 64 words
+};
+
+// One workgroup's job in the block kernel: query tile `qtile`, key tiles [begin, end) of the
+// plan-wide tile arrays.  slot < 0: the item covers the whole tile row and writes O directly;
+// slot >= 0: it writes an unnormalised partial (O, m, l) to that scratch slot.
+struct Item {
+    int32_t qtile, begin, end, slot;
+};
+
+// A query tile whose key range was split: `count` partials starting at scratch slot `slot0`.
+struct SplitRow {
+    int32_t qtile, slot0, count, pad;
+};
+
+struct DeviceArrays {
+    // row path
+    int32_t *row_ptr = nullptr;   // [n_masks][S+1], offsets local to the mask
+    int32_t *col_idx = nullptr;   // concatenated
+    int64_t *col_off = nullptr;   // [n_masks] start of each mask inside col_idx
+    // block path
+    int32_t *kt_col = nullptr, *kt_bmp = nullptr;
+    uint64_t *kt_bitmap = nullptr;
+    Item *items = nullptr;
+    int32_t *item_off = nullptr, *item_cnt = nullptr;      // [n_masks]
+    SplitRow *split_rows = nullptr;
+    int32_t *split_off = nullptr, *split_cnt = nullptr;    // [n_masks]
+};
+
+}  // namespace smha
+
+struct smha_plan {
+    int S = 0, Bm = 1, Hm = 1, block = 64;
+    smha_plan_opts_t opts{};
+    int kernel = SMHA_KERNEL_BLOCK;
+    bool has_row = false, has_block = false;
+    std::vector<smha::MaskFormats> masks;
+    double eq1_threshold = 0.0, model_row_us = 0.0, model_block_us = 0.0;
+
+    // concatenated host copies of what the kernels read
+    std::vector<int32_t> h_row_ptr, h_col_idx;
+    std::vector<int64_t> h_col_off;
+    std::vector<int32_t> h_kt_col, h_kt_bmp;
+    std::vector<uint64_t> h_kt_bitmap;
+    std::vector<smha::Item> h_items;
+    std::vector<int32_t> h_item_off, h_item_cnt;
+    std::vector<smha::SplitRow> h_split_rows;
+    std::vector<int32_t> h_split_off, h_split_cnt;
+    int max_items = 0, max_split_rows = 0, max_slots = 0;
+
+    int device = -1;  // -1: nothing uploaded
+    smha::DeviceArrays dev;
+
+    // scratch for split query tiles, grown on demand by smha_forward
+    mutable std::mutex scratch_mutex;
+    mutable float *d_scratch = nullptr;
+    mutable size_t scratch_bytes = 0;
+};
+
+namespace smha {
+
+// plan.cpp
+smha_status_t finish_plan(smha_plan *p);      // selector, work lists, concatenation
+// device.hip
+smha_status_t upload_plan(smha_plan *p, int device_id);
+void release_device(smha_plan *p);
+smha_status_t copy_mask_to_host(const uint8_t *dev_mask, size_t bytes, uint8_t *host_dst);
+int current_device_or_negative();
+
+}  // namespace smha

@@ -1,0 +1,232 @@
+"""HIP kernels against the fp64 CPU oracle, element by element, through the C ABI.
+
+Gate (fp16/bf16 inputs): max-abs <= 5e-3 and relative Frobenius <= 1e-3 on the fp32 or
+fp16 output; bf16 *output* adds its own rounding (half an ulp = 2^-9 relative), so that case
+is gated at 5e-3 + 2^-8 |ref|.  Index arrays are checked bit-exactly in test_plan_formats.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS = 5e-3
+REL_FRO = 1e-3
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+@pytest.fixture(scope="module")
+def smha():
+    import paper_2506_06095_amd as m
+    return m
+
+
+def to_dev(torch, bits, dtype):
+    t = torch.from_numpy(bits.view(np.int16)).cuda()
+    return t.view(torch.float16 if dtype == "f16" else torch.bfloat16)
+
+
+def check(got, ref, what, bf16_out=False):
+    got = got.astype(np.float64)
+    assert np.all(np.isfinite(got)), what
+    diff = np.abs(got - ref)
+    if bf16_out:
+        assert np.all(diff <= MAX_ABS + 2.0 ** -8 * np.abs(ref)), (what, diff.max())
+        return
+    fro = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    assert diff.max() <= MAX_ABS, (what, "max-abs", diff.max(), np.unravel_index(diff.argmax(), diff.shape))
+    assert fro <= REL_FRO, (what, "rel-fro", fro)
+
+
+def run_case(torch, smha, Q, K, V, dtype, masks, kernel, block=64, out_f32=False, scale=0.0,
+             heads=None, plan=None, what=""):
+    """GPU forward on everything; oracle on `heads` (list of (b, h)) or on everything."""
+    B, H, S, d = Q.shape
+    own = plan is None
+    if own:
+        plan = smha.Plan.from_dense(masks, block=block, build_both=True, head_dim=d)
+    try:
+        q, k, v = (to_dev(torch, x, dtype) for x in (Q, K, V))
+        out = plan.forward(q, k, v, out_dtype=torch.float32 if out_f32 else None, scale=scale, kernel=kernel)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+    finally:
+        if own:
+            plan.close()
+    sc = None if scale == 0.0 else scale
+    Bm, Hm = masks.shape[:2]
+    if heads is None:
+        ref = oracle.masked_attention(Q, K, V, dtype, masks, sc)
+        check(got, ref, what, bf16_out=(dtype == "bf16" and not out_f32))
+    else:
+        for (b, h) in heads:
+            m1 = np.ascontiguousarray(masks[b if Bm > 1 else 0, h if Hm > 1 else 0][None, None])
+            ref = oracle.masked_attention(*(np.ascontiguousarray(x[b:b + 1, h:h + 1]) for x in (Q, K, V)),
+                                          dtype, m1, sc)
+            check(got[b:b + 1, h:h + 1], ref, f"{what} b{b} h{h}", bf16_out=(dtype == "bf16" and not out_f32))
+    return got
+
+
+KERNELS = {"row": 1, "block": 2}
+
+
+@pytest.mark.parametrize("kernel", ["block", "row"])
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_configs_1_to_3_full_size(torch_mod, smha, idx, kernel):
+    c = W.config(idx)
+    Q, K, V = W.qkv_bits(c.B, c.H, c.S, c.d, c.dtype, c.std, c.seed)
+    masks = W.dense_mask(c.mask, c.B, c.H, c.S)
+    run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], block=c.block, what=f"{c.name}/{kernel}")
+
+
+@pytest.mark.parametrize("kernel", ["block", "row"])
+def test_config_4_bf16_full_size(torch_mod, smha, kernel):
+    c = W.config(4)
+    Q, K, V = W.qkv_bits(c.B, c.H, c.S, c.d, c.dtype, c.std, c.seed)
+    masks = W.dense_mask(c.mask, c.B, c.H, c.S)
+    heads = [(0, 0), (1, 7), (1, 15)] if kernel == "row" else None
+    with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, build_both=True, head_dim=c.d) as plan:
+        run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], out_f32=True, heads=heads,
+                 plan=plan, what=f"{c.name}/{kernel}/f32out")
+        run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], out_f32=False,
+                 heads=[(0, 3)], plan=plan, what=f"{c.name}/{kernel}/bf16out")
+
+
+def test_config_5_full_size_sampled_heads(torch_mod, smha):
+    c = W.config(5)
+    Q, K, V = W.qkv_bits(c.B, c.H, c.S, c.d, c.dtype, c.std, c.seed)
+    masks = W.dense_mask(c.mask, c.B, c.H, c.S)
+    with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, head_dim=c.d) as plan:
+        info = plan.info()
+        assert info["kernel"] == smha.SMHA_KERNEL_BLOCK and info["n_split_rows"] == 2
+        got = run_case(torch_mod, smha, Q, K, V, c.dtype, masks, 0, heads=[(0, 0), (0, 13), (0, 31)],
+                       plan=plan, what=c.name)
+    valid = c.mask.valid_len[0]
+    assert np.all(got[:, :, valid:, :] == 0.0)          # padded queries: zero rows
+    assert np.all(np.abs(got[:, :, :valid, :]).sum(axis=-1) > 0)
+
+
+@pytest.mark.parametrize("kernel", ["block", "row"])
+@pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
+def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
+    for S in (1, 37, 100, 130, 257):
+        B, H = 2, 3
+        Q, K, V = W.qkv_bits(B, H, S, d, dtype, 1.0, 1000 + S)
+        rng = np.random.default_rng(S)
+        masks = (rng.random((B, H, S, S)) < 0.35).astype(np.uint8)
+        masks[0, 0] = 0                      # nothing attends: all-zero output
+        masks[0, 1] = 1                      # dense attention
+        masks[1, 0, S // 2] = 0              # one fully masked row
+        masks[1, 1] = np.eye(S, dtype=np.uint8)  # one key per row: O = V
+        got = run_case(torch_mod, smha, Q, K, V, dtype, masks, KERNELS[kernel], out_f32=True,
+                       what=f"ragged S={S} d={d} {dtype} {kernel}")
+        assert np.all(got[0, 0] == 0.0) and np.all(got[1, 0, S // 2] == 0.0)
+        assert np.array_equal(got[1, 1].astype(np.float64), W.bits_to_f64(V, dtype)[1, 1])
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+def test_block_sizes_and_scale_and_same_dtype_output(torch_mod, smha, bs):
+    c = W.config(3)
+    B, H, S, d = 1, 2, 512, 64
+    Q, K, V = W.qkv_bits(B, H, S, d, "f16", 1.0, 77)
+    masks = W.dense_mask(c.mask, B, H, S)
+    for kernel in (1, 2):
+        run_case(torch_mod, smha, Q, K, V, "f16", masks, kernel, block=bs, scale=0.2, what=f"bs{bs} k{kernel}")
+
+
+def test_padding_per_batch_and_per_head_masks(torch_mod, smha):
+    spec = W.MaskSpec(flags=W.BIGBIRD | W.PADDING, block=64, n_window_blocks=3, n_global_blocks=1,
+                      n_random_blocks=2, seed=11, per_head=True, valid_len=(1024, 700, 1))
+    B, H, S, d = 3, 4, 1024, 128
+    Q, K, V = W.qkv_bits(B, H, S, d, "f16", 0.5, 5)
+    masks = W.dense_mask(spec, B, H, S)
+    assert masks.shape[:2] == (3, 4)
+    with smha.Plan.from_desc(spec, B, H, S, build_both=True, head_dim=d) as plan:
+        for kernel in (1, 2):
+            run_case(torch_mod, smha, Q, K, V, "f16", masks, kernel, plan=plan, what=f"padding k{kernel}")
+
+
+def test_split_rows_merge_matches_unsplit_semantics(torch_mod, smha):
+    # a few very long tile rows among short ones forces the split + combine path at d = 64
+    S, d = 4096, 64
+    spec = W.MaskSpec(flags=W.WINDOW | W.GLOBAL, window_left=32, window_right=32, n_global=70)
+    Q, K, V = W.qkv_bits(1, 2, S, d, "f16", 1.0, 8)
+    masks = W.dense_mask(spec, 1, 2, S)
+    with smha.Plan.from_desc(spec, 1, 2, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        assert plan.info()["n_split_rows"] == 2
+        run_case(torch_mod, smha, Q, K, V, "f16", masks, 0, plan=plan, what="split")
+
+
+def test_strided_tensors_device_mask_and_determinism(torch_mod, smha):
+    torch = torch_mod
+    c = W.config(2)
+    B, H, S, d = 2, 4, 512, 64
+    Q, K, V = W.qkv_bits(B, H, S, d, "f16", 1.0, 21)
+    masks = W.dense_mask(c.mask, B, H, S)
+    ref = oracle.masked_attention(Q, K, V, "f16", masks)
+    dev_mask = torch.from_numpy(masks).cuda()
+    with smha.Plan.from_dense(dev_mask, block=32, build_both=True) as plan:
+        # [B,S,H,d] storage viewed as [B,H,S,d]: non-packed strides
+        def bshd(x):
+            t = to_dev(torch, x, "f16")
+            return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        q, k, v = bshd(Q), bshd(K), bshd(V)
+        assert not q.is_contiguous()
+        for kernel in (1, 2):
+            out = torch.empty(B, S, H, d, dtype=torch.float16, device="cuda").permute(0, 2, 1, 3)
+            plan.forward(q, k, v, out=out, kernel=kernel)
+            out2 = torch.empty_like(out)
+            plan.forward(q, k, v, out=out2, kernel=kernel)
+            torch.cuda.synchronize()
+            check(out.float().cpu().numpy(), ref, f"strided k{kernel}")
+            assert torch.equal(out, out2)            # same launch twice: bit-identical
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            out3 = plan.forward(q, k, v, kernel=2, stream=side)
+        side.synchronize()
+        check(out3.float().cpu().numpy(), ref, "side stream")
+
+
+def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
+    """Scattered mask -> the calibrated selector picks row-wise and it is not slower than the
+    block kernel there; block-structured mask -> the reverse."""
+    torch = torch_mod
+
+    def time_kernel(plan, q, k, v, kernel):
+        out = plan.forward(q, k, v, kernel=kernel)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            plan.forward(q, k, v, out=out, kernel=kernel)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / 20
+
+    B, H, S, d = 4, 16, 2048, 64
+    Q, K, V = W.qkv_bits(B, H, S, d, "f16", 1.0, 31)
+    q, k, v = (to_dev(torch, x, "f16") for x in (Q, K, V))
+    scat = W.scattered_spec(S, 8, 3)
+    with smha.Plan.from_dense(scat, build_both=True) as plan:
+        assert plan.info()["kernel"] == smha.SMHA_KERNEL_ROW
+        t_row, t_blk = time_kernel(plan, q, k, v, 1), time_kernel(plan, q, k, v, 2)
+        print(f"scattered: row {t_row:.3f} ms, block {t_blk:.3f} ms")
+        assert t_row <= 1.2 * t_blk
+        run_case(torch, smha, Q, K, V, "f16", scat, 0, heads=[(0, 0), (3, 15)], plan=plan, what="scattered")
+    c = W.config(3)
+    with smha.Plan.from_desc(c.mask, B, H, S, build_both=True) as plan:
+        assert plan.info()["kernel"] == smha.SMHA_KERNEL_BLOCK
+        t_row, t_blk = time_kernel(plan, q, k, v, 1), time_kernel(plan, q, k, v, 2)
+        print(f"strided causal: row {t_row:.3f} ms, block {t_blk:.3f} ms")
+        assert t_blk <= 1.2 * t_row

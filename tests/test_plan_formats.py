@@ -1,0 +1,180 @@
+"""Host-side planner against the format oracle (bit-exact), the selector against the
+paper's formula, and the C ABI surface.  No GPU needed: plans are built host-only."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2506_06095_amd as smha
+import workloads as W
+from oracle import formats, selector
+from paper_2506_06095_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BSR_KEYS = ["load_row_ptr", "load_col_idx", "flags", "full_row_ptr", "full_col_idx",
+            "part_row_ptr", "part_col_idx"]
+
+
+def check_plan_against_oracle(plan, masks, bs):
+    Bm, Hm, S, _ = masks.shape
+    info = plan.info()
+    assert (info["S"], info["Bm"], info["Hm"], info["block"]) == (S, Bm, Hm, bs)
+    nnz = nvalid = nfull = npart = v16 = 0
+    for mi in range(Bm * Hm):
+        M = masks[mi // Hm, mi % Hm]
+        f = formats.bsr(M, bs)
+        for k in BSR_KEYS:
+            got = plan.export(k, mi)
+            assert got.dtype == f[k].dtype and np.array_equal(got, f[k]), (k, mi)
+        assert np.array_equal(plan.export("bitmap", mi).reshape(-1, bs), f["bitmap"]), mi
+        rp, ci = formats.csr(M)
+        assert np.array_equal(plan.export("row_ptr", mi), rp)
+        assert np.array_equal(plan.export("col_idx", mi), ci)
+        if bs == 64:
+            assert np.array_equal(plan.export("bitmap_it8", mi).reshape(-1, 64),
+                                  formats.bitmap_inner_tiles(f["bitmap"]))
+        nnz += f["nnz"]
+        nvalid += len(f["load_col_idx"]); nfull += len(f["full_col_idx"]); npart += len(f["part_col_idx"])
+        v16 += selector.valid16(M)
+    assert (info["nnz"], info["n_valid"], info["n_full"], info["n_part"], info["n_valid16"]) == \
+           (nnz, nvalid, nfull, npart, v16)
+    thr = selector.threshold(v16 / (Bm * Hm), S)
+    assert info["eq1_threshold"] == pytest.approx(thr, abs=1e-12) or (np.isinf(thr) and np.isinf(info["eq1_threshold"]))
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_benchmark_configs_dense_and_description_plans_match_oracle(idx):
+    c = W.config(idx)
+    masks = W.dense_mask(c.mask, c.B, c.H, c.S)
+    if idx == 4:
+        masks = masks[:, :3].copy()  # three of the sixteen per-head masks keep this quick
+    with smha.Plan.from_dense(masks, block=c.block, build_both=True, device_id=-2, head_dim=c.d) as p:
+        check_plan_against_oracle(p, masks, c.block)
+    H = 3 if idx == 4 else c.H
+    with smha.Plan.from_desc(c.mask, c.B, H, c.S, block=c.block, build_both=True, device_id=-2,
+                             head_dim=c.d) as p:
+        check_plan_against_oracle(p, masks, c.block)
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+@pytest.mark.parametrize("S", [1, 15, 64, 100, 130, 257])
+def test_ragged_sizes_and_all_block_sizes(S, bs):
+    rng = np.random.default_rng(S * 100 + bs)
+    masks = (rng.random((2, 2, S, S)) < 0.3).astype(np.uint8)
+    masks[0, 0] = 0                       # an empty mask
+    masks[0, 1] = 1                       # a dense mask
+    masks[1, 0, :, : S // 2] = 7          # nonzero bytes other than 1 count as "attend"
+    with smha.Plan.from_dense(masks, block=bs, build_both=True, device_id=-2) as p:
+        check_plan_against_oracle(p, (masks != 0).astype(np.uint8), bs)
+
+
+def test_description_patterns_match_dense_generators():
+    S = 300
+    specs = [
+        W.MaskSpec(flags=0),
+        W.MaskSpec(flags=W.CAUSAL),
+        W.MaskSpec(flags=W.WINDOW, window_left=5, window_right=0),
+        W.MaskSpec(flags=W.WINDOW | W.GLOBAL, window_left=9, window_right=3, n_global=4),
+        W.MaskSpec(flags=W.CAUSAL | W.STRIDED, stride=7, stride_phase=3),
+        W.MaskSpec(flags=W.BLOCK_RANDOM, block=24, keep_p=0.3, seed=99, per_head=True),
+        W.MaskSpec(flags=W.BIGBIRD | W.CAUSAL, block=16, n_window_blocks=3, n_global_blocks=1,
+                   n_random_blocks=2, seed=5, per_head=True),
+        W.MaskSpec(flags=W.BIGBIRD | W.PADDING, block=32, n_window_blocks=1, n_global_blocks=2,
+                   n_random_blocks=30, seed=6, valid_len=(300, 17, 0)),
+        W.MaskSpec(flags=W.WINDOW | W.PADDING, window_left=400, window_right=400, valid_len=(1, 299, 150)),
+    ]
+    for spec in specs:
+        B, H = 3, 2
+        masks = W.dense_mask(spec, B, H, S)
+        with smha.Plan.from_desc(spec, B, H, S, block=32, build_both=True, device_id=-2) as p:
+            check_plan_against_oracle(p, masks, 32)
+
+
+def test_selector_follows_eq1_and_can_be_forced():
+    c = W.config(3)
+    with smha.Plan.from_desc(c.mask, 1, 1, c.S, selector=smha.SMHA_SELECTOR_PAPER_EQ1, device_id=-2) as p:
+        i = p.info()
+        assert i["kernel"] == smha.SMHA_KERNEL_BLOCK and i["eq1_threshold"] > 0
+        assert not i["has_row_format"]
+        with pytest.raises(smha.SmhaError):
+            p.export("row_ptr")
+    # one 16x16 tile per tile row at S = 4096: 1/256 - 1.2/64 < 0 -> row-wise
+    diag = W.MaskSpec(flags=W.WINDOW)
+    with smha.Plan.from_desc(diag, 1, 1, 4096, selector=smha.SMHA_SELECTOR_PAPER_EQ1, device_id=-2) as p:
+        i = p.info()
+        assert i["kernel"] == smha.SMHA_KERNEL_ROW and i["eq1_threshold"] == pytest.approx(1 / 256 - 1.2 / 64)
+        assert i["has_row_format"] and not i["has_block_kernel_lists"]
+    with smha.Plan.from_desc(diag, 1, 1, 16, selector=smha.SMHA_SELECTOR_PAPER_EQ1, device_id=-2) as p:
+        assert p.info()["kernel"] == smha.SMHA_KERNEL_ROW
+    with smha.Plan.from_desc(diag, 1, 1, 4096, force=smha.SMHA_KERNEL_BLOCK, device_id=-2) as p:
+        assert p.info()["kernel"] == smha.SMHA_KERNEL_BLOCK
+    # calibrated model: scattered columns -> row-wise, block-structured -> block-wise
+    scat = W.scattered_spec(2048, 8, 3)
+    with smha.Plan.from_dense(scat, device_id=-2) as p:
+        assert p.info()["kernel"] == smha.SMHA_KERNEL_ROW
+    from dataclasses import replace
+    bb = replace(W.config(5).mask, valid_len=(2000,))
+    with smha.Plan.from_desc(bb, 1, 1, 2048, head_dim=128, device_id=-2) as p:
+        assert p.info()["kernel"] == smha.SMHA_KERNEL_BLOCK
+
+
+def test_work_items_cover_every_tile_exactly_once():
+    c = W.config(5)
+    with smha.Plan.from_desc(c.mask, 1, 1, c.S, device_id=-2) as p:
+        i = p.info()
+        assert i["n_split_rows"] == 2             # the two global tile rows
+        assert i["n_tiles64"] == i["n_valid"]
+        assert i["n_items"] > 128
+
+
+def test_error_paths_return_status_codes():
+    ones = np.ones((1, 1, 8, 8), np.uint8)
+    with pytest.raises(smha.SmhaError) as e:
+        smha.Plan.from_dense(ones, block=48, device_id=-2)
+    assert e.value.status == 2
+    with pytest.raises(smha.SmhaError) as e:
+        smha.Plan.from_dense(ones, force=9, device_id=-2)
+    assert e.value.status == 1
+    with pytest.raises(smha.SmhaError) as e:
+        smha.Plan.from_desc(W.MaskSpec(flags=W.STRIDED, stride=0), 1, 1, 8, device_id=-2)
+    assert e.value.status == 1
+    with pytest.raises(smha.SmhaError) as e:
+        smha.Plan.from_desc(W.MaskSpec(flags=W.PADDING), 1, 1, 8, device_id=-2)
+    assert e.value.status == 1
+    with pytest.raises(smha.SmhaError) as e:
+        smha.Plan.from_desc(W.MaskSpec(flags=W.PADDING, valid_len=(9,)), 1, 1, 8, device_id=-2)
+    assert e.value.status == 1
+    lib = binding._load()
+    assert lib.smha_plan_from_dense(None, 0, 1, 1, 8, None, None) == 1
+    assert lib.smha_plan_info(None, None) == 1
+    lib.smha_plan_destroy(None)
+    assert smha.smha_status_string(0) == "ok" and "unknown" in smha.smha_status_string(77)
+    # a host-only plan cannot run: forward must say so rather than fall back to anything
+    with smha.Plan.from_dense(ones, device_id=-2) as p:
+        buf = (ctypes.c_char * 4096)()
+        addr = (ctypes.addressof(buf) + 15) & ~15
+        st = lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 64, 0, 0,
+                              None, None, None, None, 0.0, 0, None)
+        assert st == 5
+        assert lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 48, 0, 0,
+                                None, None, None, None, 0.0, 0, None) == 2
+        assert lib.smha_forward(ctypes.c_void_p(p.handle), addr + 2, addr, addr, addr, 1, 1, 64, 0, 0,
+                                None, None, None, None, 0.0, 0, None) == 2
+        assert lib.smha_forward(ctypes.c_void_p(p.handle), None, addr, addr, addr, 1, 1, 64, 0, 0,
+                                None, None, None, None, 0.0, 0, None) == 1
+    with smha.Plan.from_dense(np.ones((2, 3, 8, 8), np.uint8), device_id=-2) as p:
+        st = lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 4, 3, 64, 0, 0,
+                              None, None, None, None, 0.0, 0, None)
+        assert st == 3
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "smha.h")).read()
+    names = set(re.findall(r"\b(smha_[a-z_0-9]+)\s*\(", text))
+    assert {"smha_plan_from_dense", "smha_plan_from_desc", "smha_plan_info", "smha_plan_export",
+            "smha_forward", "smha_plan_destroy", "smha_status_string", "smha_kernel_name"} <= names
+    lib = ctypes.CDLL(smha.library_path())
+    for n in names:
+        assert hasattr(lib, n), n
