@@ -267,7 +267,12 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
         const float mc = m_use * p.c;
         m_run = m_new;
         float psum = 0.f;
+        // P as 16-bit MFMA operands.  binary16 keeps 11 significant bits, enough for the
+        // output tolerance; bfloat16 keeps 8, which alone would cost ~1e-3 relative error, so
+        // for bf16 inputs P is split into a truncated high part and a rounded residual
+        // (p = hi + lo up to 2^-17) and the second product runs twice.
         u32x4 pf[2][2];
+        u32x4 pf_lo[BF16 ? 2 : 1][2];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -277,7 +282,15 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
                     const float e0 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q], p.c, -mc));
                     const float e1 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q + 1], p.c, -mc));
                     psum += e0 + e1;
-                    pf[kt][u][q] = pack2<BF16>(e0, e1);
+                    if constexpr (BF16) {
+                        const uint32_t b0 = __builtin_bit_cast(uint32_t, e0) & 0xFFFF0000u;
+                        const uint32_t b1 = __builtin_bit_cast(uint32_t, e1) & 0xFFFF0000u;
+                        pf[kt][u][q] = (b0 >> 16) | b1;
+                        pf_lo[kt][u][q] = pack2<true>(e0 - __builtin_bit_cast(float, b0),
+                                                      e1 - __builtin_bit_cast(float, b1));
+                    } else {
+                        pf[kt][u][q] = pack2<false>(e0, e1);
+                    }
                 }
         l_run = l_run * alpha + psum;
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
@@ -298,6 +311,7 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
                     const int chunk = (2 * (2 * kt + u) + hh) ^ sw;
                     u32x4 a = *reinterpret_cast<const u32x4 *>(&Vt[dcol * 64 + chunk * 8]);
                     o[dt] = mfma32<BF16>(a, pf[kt][u], o[dt]);
+                    if constexpr (BF16) o[dt] = mfma32<BF16>(a, pf_lo[kt][u], o[dt]);
                 }
         }
     }

@@ -131,7 +131,8 @@ def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
         got = run_case(torch_mod, smha, Q, K, V, dtype, masks, KERNELS[kernel], out_f32=True,
                        what=f"ragged S={S} d={d} {dtype} {kernel}")
         assert np.all(got[0, 0] == 0.0) and np.all(got[1, 0, S // 2] == 0.0)
-        assert np.array_equal(got[1, 1].astype(np.float64), W.bits_to_f64(V, dtype)[1, 1])
+        # one key per row: the only weight is 1 up to fp32 rounding of the exponent argument
+        assert np.allclose(got[1, 1].astype(np.float64), W.bits_to_f64(V, dtype)[1, 1], rtol=1e-5, atol=1e-7)
 
 
 @pytest.mark.parametrize("bs", [16, 32, 64])
