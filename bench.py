@@ -36,6 +36,9 @@ def main() -> int:
     ap.add_argument("--kernel", choices=["auto", "row", "block"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = auto)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (outside the timed region) so that "
+                         "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE can be scaled against known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; every (batch, head) pair is independent, so a "
@@ -69,6 +72,12 @@ def main() -> int:
     kernel = "row" if info["kernel"] == smha.SMHA_KERNEL_ROW else "block"
 
     stream = torch.cuda.current_stream()
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         plan.forward(q, k, v, out=out)
     torch.cuda.synchronize()
@@ -119,7 +128,7 @@ def main() -> int:
         masks = W.dense_mask(c.mask, B, H, S)
         Bm, Hm = masks.shape[:2]
         flat = [(b, h) for b in range(B) for h in range(H)]
-        n_heads = args.cpu_heads or max(1, min(len(flat), int(round(2.0e10 / (nnz_flops / len(flat))))))
+        n_heads = args.cpu_heads or max(1, min(len(flat), int(round(1.0e12 / (nnz_flops / len(flat))))))
         step = max(1, len(flat) // n_heads)
         sample = flat[::step][:n_heads]
         got = out.float().cpu().numpy()

@@ -101,7 +101,9 @@ typedef struct {
     int64_t n_valid, n_full, n_part; /* tiles of edge `block`, summed over masks                 */
     int64_t n_valid16;  /* non-empty 16x16 tiles, summed over masks (input of Eq. 1)             */
     int64_t n_tiles64;  /* non-empty 64x64 tiles the block kernel visits, summed over masks      */
-    int64_t n_items, n_split_rows; /* block-kernel work items / query tiles split along keys     */
+    int64_t n_union;    /* K/V tile loads of the block kernel: union of the tile lists of the two
+                           tile rows each 128-row workgroup covers, summed over masks             */
+    int64_t n_items, n_split_rows; /* block-kernel work items / 128-row groups split along keys  */
     double eq1_threshold; /* Eq. 1 with valid16 averaged over masks; < 0 means row-wise          */
     double model_row_us, model_block_us; /* calibrated cost model, per (batch, head) pair         */
 } smha_plan_info_t;

@@ -51,7 +51,7 @@ class PlanInfo(C.Structure):
                 ("kernel", C.c_int), ("has_row_format", C.c_int),
                 ("has_block_kernel_lists", C.c_int), ("on_device", C.c_int),
                 ("nnz", C.c_int64), ("n_valid", C.c_int64), ("n_full", C.c_int64),
-                ("n_part", C.c_int64), ("n_valid16", C.c_int64), ("n_tiles64", C.c_int64),
+                ("n_part", C.c_int64), ("n_valid16", C.c_int64), ("n_tiles64", C.c_int64), ("n_union", C.c_int64),
                 ("n_items", C.c_int64), ("n_split_rows", C.c_int64),
                 ("eq1_threshold", C.c_double), ("model_row_us", C.c_double),
                 ("model_block_us", C.c_double)]

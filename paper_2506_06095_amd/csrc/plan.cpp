@@ -430,36 +430,52 @@ smha_status_t finish_plan(smha_plan *p) {
         // ---- block path: tiles, work items, split rows ---------------------------
         if (p->has_block) {
             const int nqt = (S + kTile - 1) / kTile;
+            const int nsup = (S + kSuper - 1) / kSuper;
             for (int mi = 0; mi < n_masks; ++mi) {
                 MaskFormats &m = p->masks[mi];
-                const int32_t tile_base = (int32_t)p->h_kt_col.size();
                 const int32_t bmp_base = (int32_t)(p->h_kt_bitmap.size() / 64);
-                p->h_kt_col.insert(p->h_kt_col.end(), m.kt_col.begin(), m.kt_col.end());
-                for (int32_t b : m.kt_bmp) p->h_kt_bmp.push_back(b < 0 ? -1 : b + bmp_base);
                 p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), m.kt_bitmap.begin(), m.kt_bitmap.end());
-
-                // split query tiles whose tile list is much longer than the typical one, so
-                // that a few heavy rows (global tokens) do not serialise on one workgroup
+                // union of the two tile rows of every supertile (both lists ascending: merge)
+                std::vector<int32_t> sup_ptr(nsup + 1, 0);
+                const int32_t ent_base = (int32_t)p->h_uent.size();
+                for (int sp = 0; sp < nsup; ++sp) {
+                    const int r0 = 2 * sp, r1 = 2 * sp + 1;
+                    int a = m.kt_row_ptr[r0], ae = m.kt_row_ptr[r0 + 1];
+                    int b = r1 < nqt ? m.kt_row_ptr[r1] : 0, be = r1 < nqt ? m.kt_row_ptr[r1 + 1] : 0;
+                    auto code = [&](int e) { return m.kt_bmp[e] < 0 ? -1 : m.kt_bmp[e] + bmp_base; };
+                    while (a < ae || b < be) {
+                        UEntry u{0, {-2, -2}, 0};
+                        const int ca = a < ae ? m.kt_col[a] : INT32_MAX;
+                        const int cb = b < be ? m.kt_col[b] : INT32_MAX;
+                        u.col = std::min(ca, cb);
+                        if (ca == u.col) u.code[0] = code(a++);
+                        if (cb == u.col) u.code[1] = code(b++);
+                        p->h_uent.push_back(u);
+                    }
+                    sup_ptr[sp + 1] = (int32_t)p->h_uent.size() - ent_base;
+                }
+                // split supertiles whose list is much longer than the typical one, so that a
+                // few heavy rows (global tokens) do not serialise on one workgroup
                 int64_t n_nonempty = 0;
-                for (int q = 0; q < nqt; ++q) n_nonempty += m.kt_row_ptr[q + 1] > m.kt_row_ptr[q];
-                const double avg = n_nonempty ? (double)m.kt_col.size() / n_nonempty : 0.0;
-                const int chunk = std::max(16, (int)std::ceil(2.0 * avg));
+                for (int sp = 0; sp < nsup; ++sp) n_nonempty += sup_ptr[sp + 1] > sup_ptr[sp];
+                const double avg = n_nonempty ? (double)sup_ptr[nsup] / n_nonempty : 0.0;
+                const int chunk = std::max(16, (int)std::ceil(1.5 * avg));
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
-                for (int q = 0; q < nqt; ++q) {
-                    const int32_t b = tile_base + m.kt_row_ptr[q], e = tile_base + m.kt_row_ptr[q + 1];
+                for (int sp = 0; sp < nsup; ++sp) {
+                    const int32_t b = ent_base + sup_ptr[sp], e = ent_base + sup_ptr[sp + 1];
                     const int n = e - b;
                     if (n <= chunk) {
-                        items.push_back({q, b, e, -1});
+                        items.push_back({sp, b, e, -1});
                         continue;
                     }
                     const int parts = (n + chunk - 1) / chunk;
-                    splits.push_back({q, slots, parts, 0});
+                    splits.push_back({sp, slots, parts, 0});
                     for (int c = 0; c < parts; ++c) {
                         const int32_t cb = b + (int32_t)((int64_t)n * c / parts);
                         const int32_t ce = b + (int32_t)((int64_t)n * (c + 1) / parts);
-                        items.push_back({q, cb, ce, slots++});
+                        items.push_back({sp, cb, ce, slots++});
                     }
                 }
                 std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
@@ -595,6 +611,7 @@ extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *
         i.n_valid16 += m.n_valid16;
         i.n_tiles64 += (int64_t)m.kt_col.size();
     }
+    i.n_union = (int64_t)p->h_uent.size();
     i.n_items = (int64_t)p->h_items.size();
     i.n_split_rows = (int64_t)p->h_split_rows.size();
     i.eq1_threshold = p->eq1_threshold;

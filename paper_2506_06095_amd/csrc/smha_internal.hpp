@@ -9,7 +9,8 @@
 
 namespace smha {
 
-constexpr int kTile = 64;  // query rows per work item and keys per K/V tile of the block kernel
+constexpr int kTile = 64;    // keys per K/V tile and query rows per wave of the block kernel
+constexpr int kSuper = 128;  // query rows per workgroup: two vertically adjacent tile rows
 
 // Formats of one distinct mask (Sec. 4.2.1 of the paper for the block arrays).
 struct MaskFormats {
@@ -26,14 +27,22 @@ struct MaskFormats {
     std::vector<uint64_t> kt_bitmap;                       // n_part64 * 64 words
 };
 
-// One workgroup's job in the block kernel: query tile `qtile`, key tiles [begin, end) of the
-// plan-wide tile arrays.  slot < 0: the item covers the whole tile row and writes O directly;
-// slot >= 0: it writes an unnormalised partial (O, m, l) to that scratch slot.
+// The block kernel walks, per 128-row query supertile, the UNION of the key tiles of its two
+// 64-row tile rows, so that one staged K/V tile serves both.  code[w] tells wave w (tile row
+// 2*super + w) what the tile is for it: -2 = empty (skip), -1 = full, >= 0 = index of its
+// 64-word bitmap.
+struct UEntry {
+    int32_t col, code[2], pad;
+};
+
+// One workgroup's job: supertile `qtile`, union entries [begin, end).  slot < 0: the item
+// covers the whole list and writes O directly; slot >= 0: it writes an unnormalised partial
+// (O, m, l) of 128 rows to that scratch slot.
 struct Item {
     int32_t qtile, begin, end, slot;
 };
 
-// A query tile whose key range was split: `count` partials starting at scratch slot `slot0`.
+// A supertile whose list was split: `count` partials starting at scratch slot `slot0`.
 struct SplitRow {
     int32_t qtile, slot0, count, pad;
 };
@@ -44,7 +53,7 @@ struct DeviceArrays {
     int32_t *col_idx = nullptr;   // concatenated
     int64_t *col_off = nullptr;   // [n_masks] start of each mask inside col_idx
     // block path
-    int32_t *kt_col = nullptr, *kt_bmp = nullptr;
+    UEntry *uent = nullptr;
     uint64_t *kt_bitmap = nullptr;
     Item *items = nullptr;
     int32_t *item_off = nullptr, *item_cnt = nullptr;      // [n_masks]
@@ -65,7 +74,7 @@ struct smha_plan {
     // concatenated host copies of what the kernels read
     std::vector<int32_t> h_row_ptr, h_col_idx;
     std::vector<int64_t> h_col_off;
-    std::vector<int32_t> h_kt_col, h_kt_bmp;
+    std::vector<smha::UEntry> h_uent;
     std::vector<uint64_t> h_kt_bitmap;
     std::vector<smha::Item> h_items;
     std::vector<int32_t> h_item_off, h_item_cnt;

@@ -108,7 +108,7 @@ def test_config_5_full_size_sampled_heads(torch_mod, smha):
     masks = W.dense_mask(c.mask, c.B, c.H, c.S)
     with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, head_dim=c.d) as plan:
         info = plan.info()
-        assert info["kernel"] == smha.SMHA_KERNEL_BLOCK and info["n_split_rows"] == 2
+        assert info["kernel"] == smha.SMHA_KERNEL_BLOCK and info["n_split_rows"] == 1
         got = run_case(torch_mod, smha, Q, K, V, c.dtype, masks, 0, heads=[(0, 0), (0, 13), (0, 31)],
                        plan=plan, what=c.name)
     valid = c.mask.valid_len[0]
@@ -164,7 +164,7 @@ def test_split_rows_merge_matches_unsplit_semantics(torch_mod, smha):
     Q, K, V = W.qkv_bits(1, 2, S, d, "f16", 1.0, 8)
     masks = W.dense_mask(spec, 1, 2, S)
     with smha.Plan.from_desc(spec, 1, 2, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
-        assert plan.info()["n_split_rows"] == 2
+        assert plan.info()["n_split_rows"] == 1
         run_case(torch_mod, smha, Q, K, V, "f16", masks, 0, plan=plan, what="split")
 
 
