@@ -13,6 +13,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 
 #include "smha_internal.hpp"
 
@@ -50,6 +51,9 @@ struct FwdParams {
     const int32_t *row_ptr, *col_idx;
     const int64_t *col_off;
     int wgs_per_bh;
+#ifdef SMHA_DEV
+    int dbg;  // development-only switches (timing experiments)
+#endif
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -104,12 +108,15 @@ __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dt
 // ---------------------------------------------------------------------------------------
 // Block-wise kernel
 // ---------------------------------------------------------------------------------------
-// One workgroup = two waves = one 128-row query supertile; wave w owns the 64-row tile row
-// 2*super + w as two 32-row slices, so every K / V^T fragment read from LDS feeds two MFMAs.
-// The workgroup walks the union of the two tile rows' key-tile lists; a wave skips the math
-// of tiles that are empty for its own tile row but still helps staging them.
+// One workgroup = four waves = one 128-row query supertile (two vertically adjacent 64-row
+// tile rows); wave w owns rows 32 w .. 32 w + 31.  The workgroup walks the union of the two
+// tile rows' key-tile lists, so a staged K/V tile is shared by up to four waves; a wave skips
+// the math of tiles that are empty for its own tile row (or, through the bitmap, for its own
+// 32 rows) but still helps staging them.  Two workgroups fit a CU (two waves per SIMD): one
+// workgroup's softmax (vector ALU) overlaps the other's MFMAs.
 //
-// LDS layouts (16-bit elements):
+// LDS layouts (16-bit elements), both double-buffered: tile t+1 is written while tile t is
+// computed (one barrier per tile) and tile t+2 is already on its way from global memory.
 //   Ks[key][D + 8]         row-major, 16-byte pad per row -> conflict-free 16-byte operand reads
 //   Vt[dcol][64 positions] transposed; the 64 keys of a tile are permuted inside each group of
 //     16 (key = 16g + 8a + 4h + b  ->  position 16g + 8h + 4a + b) so that the 8 keys a lane
@@ -117,18 +124,9 @@ __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dt
 //     (dcol ^ dcol>>3) & 7 so that both the transposing writes and the operand reads spread
 //     over the banks.
 //
-// Software pipeline (one wave per SIMD, so overlap has to come from inside the wave).  A
-// tile is processed as two half tiles of 32 keys:
-//     scores(0) | scores(1) + probabilities(0) | P V(0) + probabilities(1) | P V(1)
-// so the vector ALU work of a half always has matrix work of its neighbour to hide under.
-// K and V^T are double-buffered in LDS: tile t+1 is written while tile t is computed (one
-// barrier per tile) and tile t+2 is already on its way from global memory into registers.
-//
-// Online softmax with a lazily raised reference: probabilities are formed against the
-// running reference m_run without waiting for the half tile's own maximum; the maximum is
-// gathered on the side and only if some row exceeds m_run by more than 2^8 is the half
-// redone against the raised reference (and O, l rescaled).  Probabilities therefore stay
-// below 2^8: exact enough in the fp32 sums and far inside the binary16 range.
+// Online softmax with a lazily raised reference: the running reference m_run is only raised
+// when a tile's row maximum exceeds it by more than 2^8, so the O rescale is rare and
+// probabilities stay below 2^8 (exact enough in the fp32 sums, far inside the binary16 range).
 __device__ __forceinline__ int vt_swz(int dcol) { return (dcol ^ (dcol >> 3)) & 7; }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, int64_t bytes) {
@@ -138,23 +136,35 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, int byte_o
     return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);  // out of range -> zeros
 }
 
-template <int V>
-struct IC {
-    static constexpr int value = V;
-};
+// Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() would also
+// drain the global loads that are deliberately left in flight across the barrier (the K/V
+// tile two steps ahead); those are consumed through registers, which the compiler tracks.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
-template <int D, bool BF16>
-__global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
+template <int OUT>  // smha_dtype_t of the output
+__device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float b, float c, float d) {
+    if constexpr (OUT == SMHA_F32) {
+        f32x4 v = {a, b, c, d};
+        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(O) + elem_off) = v;
+    } else {
+        u32x2 v = {pack2<OUT == SMHA_BF16>(a, b), pack2<OUT == SMHA_BF16>(c, d)};
+        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off) = v;
+    }
+}
+
+template <int D, bool BF16, int OUT>
+__global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
     constexpr int KSTR = D + 8;           // padded K row, in elements
     constexpr int KBUF = 64 * KSTR;       // one K buffer, in elements
-    constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
-    constexpr int KCH = 64 * CPR / 128;   // K chunks staged per thread
-    constexpr int VSU = 16 * CPR / 128;   // V sub-units (4 keys x 8 columns) per thread
-    constexpr int NP = BF16 ? 2 : 1;      // P operands per product (hi, lo for bfloat16)
-    constexpr int PPM = 16 / (2 * NS);    // probability pairs handled per score MFMA
     constexpr int VBUF = D * 64;          // one V^T buffer, in elements
+    constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
+    constexpr int KCH = 64 * CPR / 256;   // K chunks staged per thread
+    constexpr int NVU = 16 * CPR;         // V sub-units (4 keys x 8 columns) per tile: 256 or 128
+    constexpr int NP = BF16 ? 2 : 1;      // P operands per product (hi, lo for bfloat16)
     __shared__ __attribute__((aligned(16))) uint16_t Ks[2 * KBUF];
     __shared__ __attribute__((aligned(16))) uint16_t Vt[2 * VBUF];
 
@@ -184,59 +194,68 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
     const __amdgpu_buffer_rsrc_t rV = make_rsrc(p.V + b * p.vs.b + h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
     const int ksb = (int)p.ks.s * 2, vsb = (int)p.vs.s * 2;  // row pitch in bytes
 
-    // Q^T operands: slice a, lane (j, hh) holds Q[q0 + 32 a + j][16 s + 8 hh .. +8]
-    const int q0 = (2 * item.qtile + w) * 64;
-    u32x4 qf[2][NS];
+    // Q^T operand: lane (j, hh) holds Q[q0 + j][16 s + 8 hh .. +8]; rows past S read as zeros
+    const int q0 = item.qtile * 128 + 32 * w;
+    u32x4 qf[NS];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-            qf[a][s] = buf_load16(rQ, (q0 + 32 * a + j) * (int)p.qs.s * 2 + (16 * s + 8 * hh) * 2);
+    for (int s = 0; s < NS; ++s) qf[s] = buf_load16(rQ, (q0 + j) * (int)p.qs.s * 2 + (16 * s + 8 * hh) * 2);
 
-    // per-thread staging offsets
-    int kvo[KCH], vvo[VSU];
+    // The item's entries are fetched 64 at a time, one per lane, and broadcast with readlane:
+    // a dependent global load per tile would otherwise sit on the critical path.
+    int e_col = 0, e_code = -2, col_base = 0, code_base = 0;
+    auto fetch_cols = [&](int base) __attribute__((always_inline)) {
+        col_base = base;
+        if (base + lane < n) e_col = p.uent[item.begin + base + lane].col;
+    };
+    auto fetch_codes = [&](int base) __attribute__((always_inline)) {
+        code_base = base;
+        e_code = (base + lane < n) ? p.uent[item.begin + base + lane].code[w >> 1] : -2;
+    };
+    auto entry_col = [&](int t) __attribute__((always_inline)) {
+        if (t >= col_base + 64) fetch_cols(col_base + 64);
+        return __builtin_amdgcn_readlane(e_col, t & 63);
+    };
+    auto entry_code = [&](int t) __attribute__((always_inline)) {
+        if (t >= code_base + 64) fetch_codes(code_base + 64);
+        return __builtin_amdgcn_readlane(e_code, t & 63);
+    };
+    fetch_cols(0);
+    fetch_codes(0);
+
+    // staging: global -> registers -> LDS
+    const bool v_act = (NVU >= 256) || tid < NVU;  // threads that carry a V sub-unit
+    const int v_c = tid % CPR, v_kq = (tid / CPR) & 15;
+    int kvo[KCH];
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
-        const int u = tid + 128 * i;
+        const int u = tid + 256 * i;
         kvo[i] = (u / CPR) * ksb + (u % CPR) * 16;
     }
-#pragma unroll
-    for (int i = 0; i < VSU; ++i) {
-        const int u = tid + 128 * i;
-        vvo[i] = 4 * (u / CPR) * vsb + (u % CPR) * 16;
-    }
+    const int vvo = 4 * v_kq * vsb + v_c * 16;
     u32x4 kreg[KCH];
-    u32x4 vreg[VSU][4];
-    auto gloadK = [&](int col) __attribute__((always_inline)) {
-        const int base = col * 64 * ksb;
+    u32x4 vreg[4];
+    auto gload = [&](int col) __attribute__((always_inline)) {
+        const int kb = col * 64 * ksb, vb = col * 64 * vsb;
 #pragma unroll
-        for (int i = 0; i < KCH; ++i) kreg[i] = buf_load16(rK, kvo[i] + base);
-    };
-    auto gloadV = [&](int col) __attribute__((always_inline)) {
-        const int base = col * 64 * vsb;
+        for (int i = 0; i < KCH; ++i) kreg[i] = buf_load16(rK, kvo[i] + kb);
+        if (v_act) {
 #pragma unroll
-        for (int i = 0; i < VSU; ++i)
-#pragma unroll
-            for (int bb = 0; bb < 4; ++bb) vreg[i][bb] = buf_load16(rV, vvo[i] + base + bb * vsb);
-    };
-    auto stageK = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int u = tid + 128 * i;
-            *reinterpret_cast<u32x4 *>(&Ks[buf * KBUF + (u / CPR) * KSTR + 8 * (u % CPR)]) = kreg[i];
+            for (int bb = 0; bb < 4; ++bb) vreg[bb] = buf_load16(rV, vvo + vb + bb * vsb);
         }
     };
-    auto stageV = [&](int buf) __attribute__((always_inline)) {
+    auto stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < VSU; ++i) {
-            const int u = tid + 128 * i;
-            const int c = u % CPR, kq = u / CPR;
-            const int g = kq >> 2, a = (kq >> 1) & 1, hsel = kq & 1;
+        for (int i = 0; i < KCH; ++i) {
+            const int u = tid + 256 * i;
+            *reinterpret_cast<u32x4 *>(&Ks[buf * KBUF + (u / CPR) * KSTR + 8 * (u % CPR)]) = kreg[i];
+        }
+        if (v_act) {
+            const int g = v_kq >> 2, a = (v_kq >> 1) & 1, hsel = v_kq & 1;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int mword = e >> 1;
-                const uint32_t r0 = vreg[i][0][mword], r1 = vreg[i][1][mword];
-                const uint32_t r2 = vreg[i][2][mword], r3 = vreg[i][3][mword];
+                const uint32_t r0 = vreg[0][mword], r1 = vreg[1][mword];
+                const uint32_t r2 = vreg[2][mword], r3 = vreg[3][mword];
                 u32x2 out;
                 if (e & 1) {
                     out[0] = (r0 >> 16) | (r1 & 0xFFFF0000u);
@@ -245,18 +264,16 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
                     out[0] = (r0 & 0xFFFFu) | (r1 << 16);
                     out[1] = (r2 & 0xFFFFu) | (r3 << 16);
                 }
-                const int dcol = 8 * c + e;
+                const int dcol = 8 * v_c + e;
                 const int chunk = (2 * g + hsel) ^ vt_swz(dcol);
                 *reinterpret_cast<u32x2 *>(&Vt[buf * VBUF + dcol * 64 + chunk * 8 + a * 4]) = out;
             }
         }
     };
-    auto entry_col = [&](int t) __attribute__((always_inline)) { return p.uent[item.begin + t].col; };
-    auto entry_code = [&](int t) __attribute__((always_inline)) { return p.uent[item.begin + t].code[w]; };
 
     // LDS operand read offsets (elements)
     const int k_rd = j * KSTR + 8 * hh;  // + buf * KBUF + 32 kt * KSTR + 16 s
-    int v_rd[2][4];                      // [dt parity][2 kt + u]; + (dt & ~1) * 32 * 64
+    int v_rd[2][4];                      // [dt parity][2 kt + u]; + buf * VBUF + (dt & ~1) * 32 * 64
 #pragma unroll
     for (int par = 0; par < 2; ++par)
 #pragma unroll
@@ -265,220 +282,151 @@ __global__ void __launch_bounds__(128) smha_block_fwd(const FwdParams p) {
             v_rd[par][cu] = dcol * 64 + (((2 * cu + hh) ^ vt_swz(dcol)) * 8);
         }
 
-    float m_run[2] = {NEG_INF, NEG_INF}, l_run[2] = {0.f, 0.f};
-    f32x16 o[2][NDT];
+    float m_run = NEG_INF, l_run = 0.f;
+    f32x16 o[NDT];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[a][dt][r] = 0.f;
-    f32x16 Sh[2][2];        // [key half kt][slice a]: scores of the half tiles in flight
-    u32x4 pf[2][2][NP];     // [slice a][u][hi/lo]: probabilities of the half tile being multiplied
+    for (int dt = 0; dt < NDT; ++dt) o[dt] = zero16;
 
-    // ---- pieces of the pipeline ---------------------------------------------------------
-    float mc[2], psum[2], mt[2];
-    auto sm_begin = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            mc[a] = (m_run[a] == NEG_INF ? 0.f : m_run[a]) * p.c;
-            psum[a] = 0.f;
-            mt[a] = NEG_INF;
-        }
-    };
-    auto sm_pair = [&](f32x16 (&Sc)[2], int pair, bool track_max) __attribute__((always_inline)) {
-        const int a = pair >> 3, pr = pair & 7;
-        const float s0 = Sc[a][2 * pr], s1 = Sc[a][2 * pr + 1];
-        const float e0 = fast_exp2(fmaf(s0, p.c, -mc[a]));
-        const float e1 = fast_exp2(fmaf(s1, p.c, -mc[a]));
-        psum[a] += e0 + e1;
-        if (track_max) mt[a] = fmaxf(fmaxf(s0, s1), mt[a]);
-        if constexpr (BF16) {
-            // bfloat16 keeps 8 significant bits: P is split into a truncated high part and a
-            // rounded residual (p = hi + lo up to 2^-17) and the second product runs twice
-            const uint32_t b0 = __builtin_bit_cast(uint32_t, e0) & 0xFFFF0000u;
-            const uint32_t b1 = __builtin_bit_cast(uint32_t, e1) & 0xFFFF0000u;
-            pf[a][pr >> 2][0][pr & 3] = (b0 >> 16) | b1;
-            pf[a][pr >> 2][1][pr & 3] =
-                pack2<true>(e0 - __builtin_bit_cast(float, b0), e1 - __builtin_bit_cast(float, b1));
-        } else {
-            pf[a][pr >> 2][0][pr & 3] = pack2<false>(e0, e1);
-        }
-    };
-    // after the optimistic pass: raise the reference if some row overshot it, redo the half
-    auto sm_end = [&](f32x16 (&Sc)[2]) __attribute__((always_inline)) {
-        bool grow = (mt[0] > m_run[0] + thr_raw) || (mt[1] > m_run[1] + thr_raw);
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const float mrow = fmaxf(mt[a], __shfl_xor(mt[a], 32));
-                const float m_new = fmaxf(m_run[a], mrow);
-                const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
-                const float alpha = fast_exp2((m_run[a] - m_use) * p.c);
-                m_run[a] = m_new;
-                l_run[a] *= alpha;
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[a][dt][r] *= alpha;
-                mc[a] = m_use * p.c;
-                psum[a] = 0.f;
-            }
-#pragma unroll
-            for (int pair = 0; pair < 16; ++pair) sm_pair(Sc, pair, false);
-        }
-        l_run[0] += psum[0];
-        l_run[1] += psum[1];
-    };
-    auto apply_bitmap = [&](f32x16 (&Sx)[2], int code, int kt) __attribute__((always_inline)) {
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            const uint64_t word = p.kt_bitmap[(size_t)code * 64 + 32 * a + j];
-            const uint32_t bits = (uint32_t)(word >> (32 * kt)) >> (4 * hh);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (!((bits >> (8 * (r / 4) + (r % 4))) & 1u)) Sx[a][r] = NEG_INF;
-        }
-    };
     // one tile for this wave: K at Ks + kbase, V^T at Vt + vbase
     auto compute_tile = [&](int kbase, int vbase, int code) __attribute__((always_inline)) {
-        // scores of half 0
+        uint64_t word = ~0ull;
+        if (code >= 0) {
+            word = p.kt_bitmap[(size_t)code * 64 + 32 * (w & 1) + j];
+            if (__builtin_amdgcn_ballot_w64(word != 0) == 0) return;  // nothing for these 32 rows
+        }
+        // scores, transposed: acc[kt][r] = S[q = j][key = 32 kt + 8 (r/4) + 4 hh + r%4]
+        f32x16 acc[2] = {zero16, zero16};
+        const uint16_t *kp = &Ks[kbase + k_rd];
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const u32x4 frag = *reinterpret_cast<const u32x4 *>(kp + 32 * kt * KSTR + 16 * s);
+                acc[kt] = mfma32<BF16>(frag, qf[s], acc[kt]);
+            }
+        if (code >= 0) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const uint32_t bits = (uint32_t)(word >> (32 * kt)) >> (4 * hh);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (!((bits >> (8 * (r / 4) + (r % 4))) & 1u)) acc[kt][r] = NEG_INF;
+            }
+        }
+        float mt = NEG_INF;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int r = 0; r < 16; ++r) mt = fmaxf(mt, acc[kt][r]);
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        if (__builtin_amdgcn_ballot_w64(mt > m_run + thr_raw) != 0) {
+            const float m_new = fmaxf(m_run, mt);
+            const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
+            const float alpha = fast_exp2((m_run - m_use) * p.c);
+            m_run = m_new;
+            l_run *= alpha;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) Sh[kt][a][r] = 0.f;
-        const uint16_t *kp = &Ks[kbase + k_rd];
+            for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const u32x4 frag = *reinterpret_cast<const u32x4 *>(kp + 16 * s);
-#pragma unroll
-            for (int a = 0; a < 2; ++a) Sh[0][a] = mfma32<BF16>(frag, qf[a][s], Sh[0][a]);
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
         }
-        if (code >= 0) apply_bitmap(Sh[0], code, 0);
-        // scores of half 1 | probabilities of half 0
-        sm_begin();
+        const float mc = (m_run == NEG_INF ? 0.f : m_run) * p.c;
+        float psum = 0.f;
+        u32x4 pf[2][2][NP];  // [kt][u][hi/lo]
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const u32x4 frag = *reinterpret_cast<const u32x4 *>(kp + 32 * KSTR + 16 * s);
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                Sh[1][a] = mfma32<BF16>(frag, qf[a][s], Sh[1][a]);
-#pragma unroll
-                for (int q = 0; q < PPM; ++q) sm_pair(Sh[0], (s * 2 + a) * PPM + q, true);
-            }
-        }
-        sm_end(Sh[0]);
-        if (code >= 0) apply_bitmap(Sh[1], code, 1);
-        // P V of half 0 | probabilities of half 1 (into a second set of P registers)
-        const uint16_t *vp = &Vt[vbase];
-        u32x4 pf0[2][2][NP];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int x = 0; x < NP; ++x) pf0[a][u][x] = pf[a][u][x];
-        sm_begin();
-        {
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt) {
-                    const u32x4 frag =
-                        *reinterpret_cast<const u32x4 *>(vp + v_rd[dt & 1][u] + (dt & ~1) * 32 * 64);
-#pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        o[a][dt] = mfma32<BF16>(frag, pf0[a][u][0], o[a][dt]);
-                        if constexpr (BF16) o[a][dt] = mfma32<BF16>(frag, pf0[a][u][1], o[a][dt]);
-#pragma unroll
-                        for (int q = 0; q < 16 / (4 * NDT); ++q)
-                            sm_pair(Sh[1], ((u * NDT + dt) * 2 + a) * (16 / (4 * NDT)) + q, true);
+                for (int q = 0; q < 4; ++q) {
+                    const float e0 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q], p.c, -mc));
+                    const float e1 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q + 1], p.c, -mc));
+                    psum += e0 + e1;
+                    if constexpr (BF16) {
+                        // bfloat16 keeps 8 significant bits: P is split into a truncated high part
+                        // and a rounded residual (p = hi + lo up to 2^-17); the product runs twice
+                        const uint32_t b0 = __builtin_bit_cast(uint32_t, e0) & 0xFFFF0000u;
+                        const uint32_t b1 = __builtin_bit_cast(uint32_t, e1) & 0xFFFF0000u;
+                        pf[kt][u][0][q] = (b0 >> 16) | b1;
+                        pf[kt][u][1][q] = pack2<true>(e0 - __builtin_bit_cast(float, b0),
+                                                      e1 - __builtin_bit_cast(float, b1));
+                    } else {
+                        pf[kt][u][0][q] = pack2<false>(e0, e1);
                     }
                 }
-        }
-        sm_end(Sh[1]);
-        // P V of half 1
+        l_run += psum;
+        // O^T += V^T P^T
+        const uint16_t *vp = &Vt[vbase];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int cu = 0; cu < 4; ++cu)
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
-                const u32x4 frag =
-                    *reinterpret_cast<const u32x4 *>(vp + v_rd[dt & 1][2 + u] + (dt & ~1) * 32 * 64);
-#pragma unroll
-                for (int a = 0; a < 2; ++a) {
-                    o[a][dt] = mfma32<BF16>(frag, pf[a][u][0], o[a][dt]);
-                    if constexpr (BF16) o[a][dt] = mfma32<BF16>(frag, pf[a][u][1], o[a][dt]);
-                }
+                const u32x4 frag = *reinterpret_cast<const u32x4 *>(vp + v_rd[dt & 1][cu] + (dt & ~1) * 32 * 64);
+                o[dt] = mfma32<BF16>(frag, pf[cu >> 1][cu & 1][0], o[dt]);
+                if constexpr (BF16) o[dt] = mfma32<BF16>(frag, pf[cu >> 1][cu & 1][1], o[dt]);
             }
     };
 
     // ---- main loop: tile t from LDS buffer t&1, tile t+1 registers -> LDS, tile t+2 in flight
     if (n > 0) {
-        gloadK(entry_col(0));
-        gloadV(entry_col(0));
-        stageK(0);
-        stageV(0);
-        if (n > 1) {
-            gloadK(entry_col(1));
-            gloadV(entry_col(1));
-        }
-        __syncthreads();
+        gload(entry_col(0));
+        stage(0);
+        if (n > 1) gload(entry_col(1));
+        lds_barrier();
     }
     for (int t = 0; t < n; ++t) {
         const int buf = t & 1;
-        if (t + 1 < n) {
-            stageK(buf ^ 1);
-            stageV(buf ^ 1);
-        }
-        if (t + 2 < n) {
-            gloadK(entry_col(t + 2));
-            gloadV(entry_col(t + 2));
-        }
+#ifdef SMHA_DEV
+        if (!(p.dbg & 4))
+#endif
+        if (t + 1 < n) stage(buf ^ 1);
+#ifdef SMHA_DEV
+        if (!(p.dbg & 1))
+#endif
+        if (t + 2 < n) gload(entry_col(t + 2));
         const int code = entry_code(t);
+#ifdef SMHA_DEV
+        if (!(p.dbg & 2))
+#endif
         if (code != -2) compute_tile(buf * KBUF, buf * VBUF, code);
-        __syncthreads();
+        lds_barrier();
     }
 
-    // o[a][dt][r] = O[q = q0 + 32 a + j][d = 32 dt + 8 (r/4) + 4 hh + r%4]
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        const float l_tot = l_run[a] + __shfl_xor(l_run[a], 32);
-        const int qrow = q0 + 32 * a + j;
-        if (item.slot < 0) {
-            if (qrow < S) {
-                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-                const int64_t base = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
-#pragma unroll
-                for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4)
-                        store_out4(p.O, base + 32 * dt + 8 * g4 + 4 * hh, p.out_dtype, o[a][dt][4 * g4] * inv,
-                                   o[a][dt][4 * g4 + 1] * inv, o[a][dt][4 * g4 + 2] * inv,
-                                   o[a][dt][4 * g4 + 3] * inv);
-            }
-        } else {
-            float *sc = p.scratch + ((size_t)bh * p.max_slots + item.slot) * (size_t)(128 * D + 256);
-            const int row = 64 * w + 32 * a + j;
+    // o[dt][r] = O[q = q0 + j][d = 32 dt + 8 (r/4) + 4 hh + r%4]
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const int qrow = q0 + j;
+    if (item.slot < 0) {
+        if (qrow < S) {
+            const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+            const int64_t base = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    f32x4 v = {o[a][dt][4 * g4], o[a][dt][4 * g4 + 1], o[a][dt][4 * g4 + 2], o[a][dt][4 * g4 + 3]};
-                    *reinterpret_cast<f32x4 *>(sc + row * D + 32 * dt + 8 * g4 + 4 * hh) = v;
-                }
-            if (hh == 0) {
-                sc[128 * D + row] = m_run[a] * p.c;  // -inf stays -inf (c > 0)
-                sc[128 * D + 128 + row] = l_tot;
+                for (int g4 = 0; g4 < 4; ++g4)
+                    store4<OUT>(p.O, base + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
+                                o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
+        }
+    } else {
+        float *sc = p.scratch + ((size_t)bh * p.max_slots + item.slot) * (size_t)(128 * D + 256);
+        const int row = 32 * w + j;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
+                *reinterpret_cast<f32x4 *>(sc + row * D + 32 * dt + 8 * g4 + 4 * hh) = v;
             }
+        if (hh == 0) {
+            sc[128 * D + row] = m_run * p.c;  // -inf stays -inf (c > 0)
+            sc[128 * D + 128 + row] = l_tot;
         }
     }
 }
 
 // Merge the partial (O, m, l) of supertiles that were split along keys.  One workgroup per
 // (split supertile, 16-row slab, batch*head); thread = (row, 4 output columns).
-template <int D>
+template <int D, int OUT>
 __global__ void __launch_bounds__(16 * (D / 4)) smha_block_combine(const FwdParams p) {
     const int bh = blockIdx.z;
     const int b = bh / p.H, h = bh - b * p.H;
@@ -504,8 +452,8 @@ __global__ void __launch_bounds__(16 * (D / 4)) smha_block_combine(const FwdPara
         }
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
-    store_out4(p.O, b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s + 4 * dq, p.out_dtype, acc[0] * inv,
-               acc[1] * inv, acc[2] * inv, acc[3] * inv);
+    store4<OUT>(p.O, b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s + 4 * dq, acc[0] * inv, acc[1] * inv,
+                acc[2] * inv, acc[3] * inv);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -722,20 +670,27 @@ using namespace smha;
 
 static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0 && s[2] > 0); }
 
-template <int D, bool BF16>
-static hipError_t launch_block(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
+template <int D, bool BF16, int OUT>
+static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     const int BH = fp.B * fp.H;
     const int groups = (BH + 7) / 8;
     const unsigned grid = (unsigned)(8 * groups * plan->max_items);
     if (grid == 0) return hipSuccess;
-    hipLaunchKernelGGL((smha_block_fwd<D, BF16>), dim3(grid), dim3(128), 0, stream, fp);
+    hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT>), dim3(grid), dim3(256), 0, stream, fp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan->max_split_rows > 0) {
-        hipLaunchKernelGGL((smha_block_combine<D>), dim3(plan->max_split_rows, 8, BH), dim3(16 * (D / 4)), 0, stream, fp);
+        hipLaunchKernelGGL((smha_block_combine<D, OUT>), dim3(plan->max_split_rows, 8, BH), dim3(16 * (D / 4)), 0,
+                           stream, fp);
         e = hipGetLastError();
     }
     return e;
+}
+
+template <int D, bool BF16>
+static hipError_t launch_block(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
+    if (fp.out_dtype == SMHA_F32) return launch_block_out<D, BF16, SMHA_F32>(plan, fp, stream);
+    return launch_block_out<D, BF16, BF16 ? SMHA_BF16 : SMHA_F16>(plan, fp, stream);
 }
 
 template <int D, bool BF16>
@@ -800,6 +755,9 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     fp.split_rows = dv.split_rows; fp.split_off = dv.split_off; fp.split_cnt = dv.split_cnt;
     fp.row_ptr = dv.row_ptr; fp.col_idx = dv.col_idx; fp.col_off = dv.col_off;
 
+#ifdef SMHA_DEV
+    { const char *dbg = getenv("SMHA_DBG"); fp.dbg = dbg ? atoi(dbg) : 0; }
+#endif
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;
     if (which == SMHA_KERNEL_BLOCK) {
