@@ -26,6 +26,13 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# very command, scaled by what the same counters read for a 256 MiB device copy (FETCH_SIZE x2.0,
+# WRITE_SIZE x1.0 on this machine).  Source: profiles/smha_block_fwd_cfg5_bigbird_8k.md.
+MEASURED_TRAFFIC = {
+    ("cfg5_bigbird_8k", "block"): {"read_bytes": 303.0e6, "write_bytes": 81.0e6},
+}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -98,7 +105,8 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[c.dtype], "unit": "TFLOP/s",
                 "frac": achieved / PEAK_TFLOPS[c.dtype], "traffic": None,
                 "kernel": smha.smha_kernel_name(plan.handle, d, 0 if c.dtype == "f16" else 1),
-                "flops_per_launch": tile_flops, "launch_ms": launch_ms}
+                "flops_per_launch": tile_flops, "launch_ms": launch_ms,
+                "compulsory_hbm_bytes": 4.0 * B * H * S * d * 2}
     else:
         # Q + O once, every K/V row once, 4 bytes per unmasked entry of index, row pointers
         alg_bytes = 4.0 * B * H * S * d * 2 + 4.0 * info["nnz"] + 4.0 * (S + 1) * n_masks
@@ -108,6 +116,10 @@ def main() -> int:
                 "kernel": smha.smha_kernel_name(plan.handle, d, 0 if c.dtype == "f16" else 1),
                 "bytes_per_launch": alg_bytes, "launch_ms": launch_ms}
 
+    tr = MEASURED_TRAFFIC.get((c.name, kernel))
+    if tr is not None:
+        roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
+        roof["traffic_detail"] = dict(tr, unit="bytes per launch", source="rocprofv3 --pmc, see profiles/")
     result = {
         "metric": "masked-MHA effective TFLOP/s over unmasked entries (latency in ms_per_step)",
         "value": nnz_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
