@@ -11,6 +11,7 @@
 //   LDS and no barrier.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -41,8 +42,10 @@ struct FwdParams {
     const Item *items;
     const int32_t *item_off, *item_cnt;
     int max_items;
+    int n_work;  // 8 * ceil(B*H/8) * max_items work slots (some empty)
     const UEntry *uent;
     const uint64_t *kt_bitmap;
+    int bmp_spare;  // index of an all-zero spare bitmap block (read for tiles without a bitmap)
     float *scratch;
     int max_slots;
     const SplitRow *split_rows;
@@ -53,6 +56,7 @@ struct FwdParams {
     int wgs_per_bh;
 #ifdef SMHA_DEV
     int dbg;  // development-only switches (timing experiments)
+    unsigned long long *stamps;  // [n_work][8] cycle stamps
 #endif
 };
 
@@ -112,35 +116,43 @@ __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dt
 // tile rows); wave w owns rows 32 w .. 32 w + 31.  The workgroup walks the union of the two
 // tile rows' key-tile lists, so a staged K/V tile is shared by up to four waves; a wave skips
 // the math of tiles that are empty for its own tile row (or, through the bitmap, for its own
-// 32 rows) but still helps staging them.  Two workgroups fit a CU (two waves per SIMD): one
-// workgroup's softmax (vector ALU) overlaps the other's MFMAs.
+// 32 rows).  Two workgroups fit a CU (two waves per SIMD): one workgroup's softmax (vector
+// ALU) and memory waits overlap the other's MFMAs.
 //
-// LDS layouts (16-bit elements), both double-buffered: tile t+1 is written while tile t is
-// computed (one barrier per tile) and tile t+2 is already on its way from global memory.
-//   Ks[key][D + 8]         row-major, 16-byte pad per row -> conflict-free 16-byte operand reads
-//   Vt[dcol][64 positions] transposed; the 64 keys of a tile are permuted inside each group of
-//     16 (key = 16g + 8a + 4h + b  ->  position 16g + 8h + 4a + b) so that the 8 keys a lane
-//     needs for one MFMA are one 16-byte chunk, and chunks are XOR-swizzled by
-//     (dcol ^ dcol>>3) & 7 so that both the transposing writes and the operand reads spread
-//     over the banks.
+// K and V tiles go from global memory straight into LDS (buffer_load ... lds, 16 bytes per
+// lane, no registers and no vector-ALU work), both row-major [64 keys][D] with the 16-byte
+// chunks of a row XOR-swizzled by (row & 7) so that operand reads spread over the banks.  The
+// swizzle is applied on the global side: LDS chunk p of a row is filled with global chunk
+// p ^ (row & 7).  Rows past S read as zeros (buffer bounds), so ragged S needs no branches.
+// Both tiles are double-buffered: the loads of tile t+2 are issued right after the barrier
+// that ends tile t and are only waited for at the barrier that ends tile t+1.
+//
+// S^T = K Q^T reads K fragments with 16-byte LDS reads (a lane's 8 consecutive d values of
+// one key).  O^T = V^T P^T needs, per lane, 8 keys of one d column: ds_read_b64_tr_b16
+// delivers exactly that from the row-major tile (16 lanes read 4 keys x 16 columns, each lane
+// receives 4 keys of one column), so V is never transposed in software.
 //
 // Online softmax with a lazily raised reference: the running reference m_run is only raised
 // when a tile's row maximum exceeds it by more than 2^8, so the O rescale is rare and
 // probabilities stay below 2^8 (exact enough in the fp32 sums, far inside the binary16 range).
-__device__ __forceinline__ int vt_swz(int dcol) { return (dcol ^ (dcol >> 3)) & 7; }
-
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, int64_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
 __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, int byte_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);  // out of range -> zeros
 }
+typedef __attribute__((address_space(3))) void lds_void;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-// Workgroup barrier that waits for this wave's LDS traffic only.  __syncthreads() would also
-// drain the global loads that are deliberately left in flight across the barrier (the K/V
-// tile two steps ahead); those are consumed through registers, which the compiler tracks.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// 64 lanes x 16 bytes from per-lane global offsets into 1 KiB of LDS at `dst` (lane l -> dst + 16 l)
+__device__ __forceinline__ void load_to_lds(__amdgpu_buffer_rsrc_t r, uint16_t *dst, int byte_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)dst, 16, byte_off, 0, 0, 0);
+}
+// transposing LDS read: see the kernel comment; returns this lane's 4 keys of one column
+__device__ __forceinline__ u32x2 lds_read_tr(const uint16_t *src) {
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)src);
+    return __builtin_bit_cast(u32x2, v);
 }
 
 template <int OUT>  // smha_dtype_t of the output
@@ -154,33 +166,29 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
     }
 }
 
+#ifdef SMHA_DEV
+#define STAMP(k) do { if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)wg * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
+#define PHASE(k) do { if (p.dbg & 256) { unsigned long long now = __builtin_readcyclecounter(); ph[k] += now - tprev; tprev = now; } } while (0)
+#else
+#define STAMP(k) do { } while (0)
+#define PHASE(k) do { } while (0)
+#endif
+
 template <int D, bool BF16, int OUT>
 __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
-    constexpr int KSTR = D + 8;           // padded K row, in elements
-    constexpr int KBUF = 64 * KSTR;       // one K buffer, in elements
-    constexpr int VBUF = D * 64;          // one V^T buffer, in elements
+    constexpr int TILE = 64 * D;          // one K or V tile, in elements
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
-    constexpr int KCH = 64 * CPR / 256;   // K chunks staged per thread
-    constexpr int NVU = 16 * CPR;         // V sub-units (4 keys x 8 columns) per tile: 256 or 128
+    constexpr int LPW = CPR / 4;          // 1 KiB load instructions per wave, per tile, per tensor
     constexpr int NP = BF16 ? 2 : 1;      // P operands per product (hi, lo for bfloat16)
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[2 * KBUF];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[2 * VBUF];
-
-    // workgroup -> (batch*head, item).  Workgroups are dealt round-robin to the 8 XCDs, so
-    // the low 3 bits pick the (b,h) pair inside a group of 8: each XCD's L2 then serves the
-    // K/V of one head at a time.
-    const int wg = blockIdx.x;
-    const int xcd = wg & 7, rest = wg >> 3;
-    const int grp = rest / p.max_items, it = rest - grp * p.max_items;
-    const int bh = grp * 8 + xcd;
-    if (bh >= p.B * p.H) return;
-    const int b = bh / p.H, h = bh - b * p.H;
-    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
-    if (it >= p.item_cnt[mask]) return;
-    const Item item = p.items[p.item_off[mask] + it];
-    const int n = item.end - item.begin;
+    constexpr int PF = 4;                 // LDS fragment requests kept ahead of the MFMAs
+    // four separate LDS objects: the compiler then knows that the loads flying into one buffer
+    // cannot alias the operand reads from the other and does not wait for them
+    __shared__ __attribute__((aligned(1024))) uint16_t K0[TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t K1[TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t V0[TILE];
+    __shared__ __attribute__((aligned(1024))) uint16_t V1[TILE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -188,6 +196,40 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
     const int S = p.S;
     const float NEG_INF = -__builtin_inff();
     const float thr_raw = 8.0f / p.c;
+    constexpr int OOB = 0x7FFFFF00;  // past every buffer: such loads return zeros without traffic
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // LDS operand read offsets (elements).
+    // K fragment (kt, s): row 32 kt + j, logical chunk 2 s + hh -> physical (2s & 8) | ((2s & 7) ^ hh ^ (j & 7))
+    int k_rd[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) k_rd[c] = j * D + (((2 * c) ^ hh ^ (j & 7)) & 7) * 8;
+    // V^T fragment (dt, key group of 4): lane reads 8 bytes of row 4 hh' + (lane%16)/4 (hh' = lane/32),
+    // logical chunk 4 dt + 2 ((lane/16)&1) + (lane%4)/2, second half of the chunk if lane%4 is odd
+    const int v_row = 4 * hh + ((lane & 15) >> 2);
+    int v_rd[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+        v_rd[par] = v_row * D + (((4 * par + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ v_row) & 7) * 8 + (lane & 1) * 4;
+
+    // Persistent workgroups: the grid is a multiple of 8 that fills the chip once, and each
+    // workgroup walks the work list with that stride (so it stays on its XCD's heads); the
+    // output stores of one item drain while the next item starts.  Work index -> XCD = index
+    // mod 8 -> (batch*head) so that each XCD's L2 serves the K/V of one head at a time.
+    for (int wg = blockIdx.x; wg < p.n_work; wg += gridDim.x) {
+    STAMP(0);
+#ifdef SMHA_DEV
+    unsigned long long ph[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = 0;
+#endif
+    const int xcd = wg & 7, rest = wg >> 3;
+    const int grp = rest / p.max_items, it = rest - grp * p.max_items;
+    const int bh = grp * 8 + xcd;
+    if (bh >= p.B * p.H) continue;
+    const int b = bh / p.H, h = bh - b * p.H;
+    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
+    if (it >= p.item_cnt[mask]) continue;
+    const Item item = p.items[p.item_off[mask] + it];
+    const int n = item.end - item.begin;
 
     const __amdgpu_buffer_rsrc_t rQ = make_rsrc(p.Q + b * p.qs.b + h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
     const __amdgpu_buffer_rsrc_t rK = make_rsrc(p.K + b * p.ks.b + h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
@@ -200,111 +242,70 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) qf[s] = buf_load16(rQ, (q0 + j) * (int)p.qs.s * 2 + (16 * s + 8 * hh) * 2);
 
-    // The item's entries are fetched 64 at a time, one per lane, and broadcast with readlane:
-    // a dependent global load per tile would otherwise sit on the critical path.
-    int e_col = 0, e_code = -2, col_base = 0, code_base = 0;
-    auto fetch_cols = [&](int base) __attribute__((always_inline)) {
-        col_base = base;
-        if (base + lane < n) e_col = p.uent[item.begin + base + lane].col;
-    };
-    auto fetch_codes = [&](int base) __attribute__((always_inline)) {
-        code_base = base;
-        e_code = (base + lane < n) ? p.uent[item.begin + base + lane].code[w >> 1] : -2;
-    };
-    auto entry_col = [&](int t) __attribute__((always_inline)) {
-        if (t >= col_base + 64) fetch_cols(col_base + 64);
-        return __builtin_amdgcn_readlane(e_col, t & 63);
-    };
-    auto entry_code = [&](int t) __attribute__((always_inline)) {
-        if (t >= code_base + 64) fetch_codes(code_base + 64);
-        return __builtin_amdgcn_readlane(e_code, t & 63);
-    };
-    fetch_cols(0);
-    fetch_codes(0);
-
-    // staging: global -> registers -> LDS
-    const bool v_act = (NVU >= 256) || tid < NVU;  // threads that carry a V sub-unit
-    const int v_c = tid % CPR, v_kq = (tid / CPR) & 15;
-    int kvo[KCH];
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-        const int u = tid + 256 * i;
-        kvo[i] = (u / CPR) * ksb + (u % CPR) * 16;
+    // The item's entries (at most 64, the planner cuts longer lists) are fetched once, one per
+    // lane, and broadcast with readlane.
+    int e_col = 0, e_code = -2;
+    if (lane < n) {
+        const UEntry u = p.uent[item.begin + lane];
+        e_col = u.col;
+        e_code = u.code[w >> 1];
     }
-    const int vvo = 4 * v_kq * vsb + v_c * 16;
-    u32x4 kreg[KCH];
-    u32x4 vreg[4];
-    auto gload = [&](int col) __attribute__((always_inline)) {
-        const int kb = col * 64 * ksb, vb = col * 64 * vsb;
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) kreg[i] = buf_load16(rK, kvo[i] + kb);
-        if (v_act) {
-#pragma unroll
-            for (int bb = 0; bb < 4; ++bb) vreg[bb] = buf_load16(rV, vvo + vb + bb * vsb);
-        }
+    auto entry_col = [&](int t) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(e_col, t & 63); };
+    auto entry_code = [&](int t) __attribute__((always_inline)) {
+        return t < n ? __builtin_amdgcn_readlane(e_code, t & 63) : -2;
     };
-    auto stage = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int u = tid + 256 * i;
-            *reinterpret_cast<u32x4 *>(&Ks[buf * KBUF + (u / CPR) * KSTR + 8 * (u % CPR)]) = kreg[i];
-        }
-        if (v_act) {
-            const int g = v_kq >> 2, a = (v_kq >> 1) & 1, hsel = v_kq & 1;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int mword = e >> 1;
-                const uint32_t r0 = vreg[0][mword], r1 = vreg[1][mword];
-                const uint32_t r2 = vreg[2][mword], r3 = vreg[3][mword];
-                u32x2 out;
-                if (e & 1) {
-                    out[0] = (r0 >> 16) | (r1 & 0xFFFF0000u);
-                    out[1] = (r2 >> 16) | (r3 & 0xFFFF0000u);
-                } else {
-                    out[0] = (r0 & 0xFFFFu) | (r1 << 16);
-                    out[1] = (r2 & 0xFFFFu) | (r3 << 16);
-                }
-                const int dcol = 8 * v_c + e;
-                const int chunk = (2 * g + hsel) ^ vt_swz(dcol);
-                *reinterpret_cast<u32x2 *>(&Vt[buf * VBUF + dcol * 64 + chunk * 8 + a * 4]) = out;
-            }
-        }
+    // bitmap word of this lane's query row for a part tile; full / empty tiles read a spare block
+    auto fetch_word = [&](int code) __attribute__((always_inline)) {
+        const int blk = code >= 0 ? code : p.bmp_spare;
+        return p.kt_bitmap[(size_t)blk * 64 + 32 * (w & 1) + j];
     };
 
-    // LDS operand read offsets (elements)
-    const int k_rd = j * KSTR + 8 * hh;  // + buf * KBUF + 32 kt * KSTR + 16 s
-    int v_rd[2][4];                      // [dt parity][2 kt + u]; + buf * VBUF + (dt & ~1) * 32 * 64
+    // global -> LDS: wave w fills the 1 KiB blocks w, w+4, ... of each tile; LDS chunk (row, pc)
+    // receives global chunk pc ^ (row & 7)
+    int k_go[LPW], v_go[LPW];
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
+    for (int i = 0; i < LPW; ++i) {
+        const int pchunk = (w + 4 * i) * 64 + lane;
+        const int row = pchunk / CPR, pc = pchunk % CPR;
+        k_go[i] = row * ksb + (pc ^ (row & 7)) * 16;
+        v_go[i] = row * vsb + (pc ^ (row & 7)) * 16;
+    }
+    auto load_tile = [&](int t, uint16_t *Kd, uint16_t *Vd) __attribute__((always_inline)) {  // past the end: zeros, no traffic
+        const int col = entry_col(t);
+        const int kb = t < n ? col * 64 * ksb : OOB, vb = t < n ? col * 64 * vsb : OOB;
 #pragma unroll
-        for (int cu = 0; cu < 4; ++cu) {
-            const int dcol = 32 * par + j;
-            v_rd[par][cu] = dcol * 64 + (((2 * cu + hh) ^ vt_swz(dcol)) * 8);
+        for (int i = 0; i < LPW; ++i) {
+            load_to_lds(rK, Kd + (w + 4 * i) * 512, k_go[i] + kb);
+            load_to_lds(rV, Vd + (w + 4 * i) * 512, v_go[i] + vb);
         }
+    };
 
     float m_run = NEG_INF, l_run = 0.f;
     f32x16 o[NDT];
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt) o[dt] = zero16;
 
-    // one tile for this wave: K at Ks + kbase, V^T at Vt + vbase
-    auto compute_tile = [&](int kbase, int vbase, int code) __attribute__((always_inline)) {
-        uint64_t word = ~0ull;
-        if (code >= 0) {
-            word = p.kt_bitmap[(size_t)code * 64 + 32 * (w & 1) + j];
-            if (__builtin_amdgcn_ballot_w64(word != 0) == 0) return;  // nothing for these 32 rows
-        }
-        // scores, transposed: acc[kt][r] = S[q = j][key = 32 kt + 8 (r/4) + 4 hh + r%4]
+    // one tile for this wave
+    auto compute_tile = [&](const uint16_t *kp, const uint16_t *vp, int code, uint64_t word) __attribute__((always_inline)) {
+        if (code >= 0 && __builtin_amdgcn_ballot_w64(word != 0) == 0) return;  // nothing for these 32 rows
+        // scores, transposed: acc[kt][r] = S[q = j][key = 32 kt + 8 (r/4) + 4 hh + r%4].
+        // Fragments are requested PF MFMAs ahead of their use (LDS latency is several MFMAs).
         f32x16 acc[2] = {zero16, zero16};
-        const uint16_t *kp = &Ks[kbase + k_rd];
+        auto k_addr = [&](int i) __attribute__((always_inline)) {  // i = 2 s + kt
+            const int s = i >> 1, kt = i & 1;
+            return kp + k_rd[s & 3] + 32 * kt * D + ((2 * s) & 8) * 8;
+        };
+        u32x4 kfrag[PF];
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
+        for (int i = 0; i < PF; ++i) kfrag[i] = *reinterpret_cast<const u32x4 *>(k_addr(i));
+        __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the MFMAs that follow
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                const u32x4 frag = *reinterpret_cast<const u32x4 *>(kp + 32 * kt * KSTR + 16 * s);
-                acc[kt] = mfma32<BF16>(frag, qf[s], acc[kt]);
-            }
+        for (int i = 0; i < 2 * NS; ++i) {  // the two accumulator chains alternate
+            acc[i & 1] = mfma32<BF16>(kfrag[i % PF], qf[i >> 1], acc[i & 1]);
+            if (i + PF < 2 * NS) kfrag[i % PF] = *reinterpret_cast<const u32x4 *>(k_addr(i + PF));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        PHASE(2);
         if (code >= 0) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
@@ -314,84 +315,139 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
                     if (!((bits >> (8 * (r / 4) + (r % 4))) & 1u)) acc[kt][r] = NEG_INF;
             }
         }
-        float mt = NEG_INF;
+        // Probabilities against the current reference, optimistically: the row maximum is not
+        // needed unless some probability would exceed 2^8, and that shows in the row sum that is
+        // formed anyway.  Only then (always on an item's first tile, rarely afterwards) is the
+        // reference raised, O and l rescaled, and the key group redone.
+        float mc = (m_run == NEG_INF ? 0.f : m_run) * p.c;
+        float psum = 0.f;
+        u32x4 pf[4][NP];  // [cu = 2 kt + u: keys 16 cu .. 16 cu + 15][hi/lo]
+        auto p_pair = [&](int cu, int q, float &gs) __attribute__((always_inline)) {  // pair q (0..3) of key group cu
+            const int kt = cu >> 1, u = cu & 1;
+            const float e0 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q], p.c, -mc));
+            const float e1 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q + 1], p.c, -mc));
+            if constexpr (BF16) {
+                // bfloat16 keeps 8 significant bits: P is split into a truncated high part and a
+                // rounded residual (p = hi + lo up to 2^-17); the product runs twice
+                gs += e0 + e1;
+                const uint32_t b0 = __builtin_bit_cast(uint32_t, e0) & 0xFFFF0000u;
+                const uint32_t b1 = __builtin_bit_cast(uint32_t, e1) & 0xFFFF0000u;
+                pf[cu][0][q] = (b0 >> 16) | b1;
+                pf[cu][1][q] = pack2<true>(e0 - __builtin_bit_cast(float, b0), e1 - __builtin_bit_cast(float, b1));
+            } else {
+                // the row sum is formed from the rounded binary16 values the MFMA will use
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                const uint32_t packed = pack2<false>(e0, e1);
+                pf[cu][0][q] = packed;
+                gs = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, packed), __builtin_bit_cast(h2, 0x3C003C00u), gs, false);
+            }
+        };
+        auto raise_reference = [&]() __attribute__((always_inline)) {
+            float mt = NEG_INF;
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+            for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mt = fmaxf(mt, acc[kt][r]);
-        mt = fmaxf(mt, __shfl_xor(mt, 32));
-        if (__builtin_amdgcn_ballot_w64(mt > m_run + thr_raw) != 0) {
+                for (int r = 0; r < 16; ++r) mt = fmaxf(mt, acc[kt][r]);
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
             const float m_new = fmaxf(m_run, mt);
             const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
             const float alpha = fast_exp2((m_run - m_use) * p.c);
             m_run = m_new;
+            mc = m_use * p.c;
             l_run *= alpha;
+            psum *= alpha;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        }
-        const float mc = (m_run == NEG_INF ? 0.f : m_run) * p.c;
-        float psum = 0.f;
-        u32x4 pf[2][2][NP];  // [kt][u][hi/lo]
+        };
+        // O^T += V^T P^T.  Fragment (cu, dt): keys 16 cu + 8 a + 4 hh + 0..3 (a = 0, 1) of columns
+        // 32 dt + j: two transposing reads, requested PF MFMAs ahead.  The exponentials of key
+        // group cu+1 are issued between the MFMAs of group cu, so they run under the matrix pipe.
+        auto v_frag = [&](int i) __attribute__((always_inline)) {  // i = cu * NDT + dt
+            const int cu = i / NDT, dt = i % NDT;
+            const uint16_t *ptr = vp + v_rd[dt & 1] + (16 * cu) * D + ((4 * dt) & 8) * 8;
+            const u32x2 lo = lds_read_tr(ptr), hi = lds_read_tr(ptr + 8 * D);
+            return u32x4{lo[0], lo[1], hi[0], hi[1]};
+        };
+        u32x4 vfrag[PF];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int i = 0; i < PF; ++i) vfrag[i] = v_frag(i);
+        float gs = 0.f;
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+        for (int q = 0; q < 4; ++q) p_pair(0, q, gs);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float e0 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q], p.c, -mc));
-                    const float e1 = fast_exp2(fmaf(acc[kt][8 * u + 2 * q + 1], p.c, -mc));
-                    psum += e0 + e1;
-                    if constexpr (BF16) {
-                        // bfloat16 keeps 8 significant bits: P is split into a truncated high part
-                        // and a rounded residual (p = hi + lo up to 2^-17); the product runs twice
-                        const uint32_t b0 = __builtin_bit_cast(uint32_t, e0) & 0xFFFF0000u;
-                        const uint32_t b1 = __builtin_bit_cast(uint32_t, e1) & 0xFFFF0000u;
-                        pf[kt][u][0][q] = (b0 >> 16) | b1;
-                        pf[kt][u][1][q] = pack2<true>(e0 - __builtin_bit_cast(float, b0),
-                                                      e1 - __builtin_bit_cast(float, b1));
-                    } else {
-                        pf[kt][u][0][q] = pack2<false>(e0, e1);
-                    }
-                }
-        l_run += psum;
-        // O^T += V^T P^T
-        const uint16_t *vp = &Vt[vbase];
+        for (int cu = 0; cu < 4; ++cu) {
+            // (a row without a reference yet must get one before anything is accumulated for it)
+            if (__builtin_amdgcn_ballot_w64(!(gs <= 256.f) || m_run == NEG_INF) != 0) {
+                raise_reference();
+                gs = 0.f;
 #pragma unroll
-        for (int cu = 0; cu < 4; ++cu)
+                for (int q = 0; q < 4; ++q) p_pair(cu, q, gs);
+            }
+            psum += gs;
+            gs = 0.f;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
-                const u32x4 frag = *reinterpret_cast<const u32x4 *>(vp + v_rd[dt & 1][cu] + (dt & ~1) * 32 * 64);
-                o[dt] = mfma32<BF16>(frag, pf[cu >> 1][cu & 1][0], o[dt]);
-                if constexpr (BF16) o[dt] = mfma32<BF16>(frag, pf[cu >> 1][cu & 1][1], o[dt]);
+                const int i = cu * NDT + dt;
+                o[dt] = mfma32<BF16>(vfrag[i % PF], pf[cu][0], o[dt]);
+                if constexpr (BF16) o[dt] = mfma32<BF16>(vfrag[i % PF], pf[cu][1], o[dt]);
+                if (i + PF < 4 * NDT) vfrag[i % PF] = v_frag(i + PF);
+                if (cu < 3) {
+#pragma unroll
+                    for (int q = dt * (4 / NDT); q < (dt + 1) * (4 / NDT); ++q) p_pair(cu + 1, q, gs);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+        l_run += psum;
     };
 
-    // ---- main loop: tile t from LDS buffer t&1, tile t+1 registers -> LDS, tile t+2 in flight
+    // ---- main loop: tile t from LDS buffer t&1 while tile t+1 lands in the other buffer; the
+    // loads of tile t+2 are issued as soon as every wave has finished with tile t.  Unrolled by
+    // two so that each buffer is a compile-time object.
+    STAMP(1);
+    int code = entry_code(0);
+    uint64_t word = fetch_word(code);
     if (n > 0) {
-        gload(entry_col(0));
-        stage(0);
-        if (n > 1) gload(entry_col(1));
-        lds_barrier();
+        load_tile(0, K0, V0);
+        __builtin_amdgcn_s_waitcnt(0x0070);  // tile 0 landed (also Q, entries, first bitmap word)
+        __builtin_amdgcn_s_barrier();
+        load_tile(1, K1, V1);
     }
-    for (int t = 0; t < n; ++t) {
-        const int buf = t & 1;
+    STAMP(2);
 #ifdef SMHA_DEV
-        if (!(p.dbg & 4))
+    if (p.dbg & 256) tprev = __builtin_readcyclecounter();
 #endif
-        if (t + 1 < n) stage(buf ^ 1);
-#ifdef SMHA_DEV
-        if (!(p.dbg & 1))
-#endif
-        if (t + 2 < n) gload(entry_col(t + 2));
-        const int code = entry_code(t);
-#ifdef SMHA_DEV
-        if (!(p.dbg & 2))
-#endif
-        if (code != -2) compute_tile(buf * KBUF, buf * VBUF, code);
-        lds_barrier();
+    auto step = [&](int t, uint16_t *Kc, uint16_t *Vc) __attribute__((always_inline)) {
+        const int code_next = entry_code(t + 1);
+        const uint64_t word_next = fetch_word(code_next);
+        PHASE(0);
+        if (code != -2) compute_tile(Kc, Vc, code, word);
+        PHASE(4);
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tile t+1 landed, own LDS reads done
+        PHASE(6);
+        __builtin_amdgcn_s_barrier();        // ... for every wave: tile t+1 visible, tile t free
+        PHASE(5);
+        load_tile(t + 2, Kc, Vc);
+        PHASE(1);
+        code = code_next;
+        word = word_next;
+    };
+    for (int t = 0; t < n; t += 2) {
+        step(t, K0, V0);
+        if (t + 1 < n) step(t + 1, K1, V1);
     }
+
+    STAMP(3);
+#ifdef SMHA_DEV
+    if ((p.dbg & 256) && p.stamps && threadIdx.x == 0) { p.stamps[(size_t)wg * 8 + 5] = ph[0] + (ph[1] << 32); p.stamps[(size_t)wg * 8 + 6] = ph[2] + (ph[3] << 32); p.stamps[(size_t)wg * 8 + 7] = ph[4] + (ph[5] << 32); p.stamps[(size_t)wg * 8 + 1] = ph[6]; }
+#endif
+    // the loads of tiles n, n+1 (zeros) were issued into both buffers: let them land before the
+    // next item overwrites the buffers (before the output stores, which may then drain freely)
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __builtin_amdgcn_s_barrier();
 
     // o[dt][r] = O[q = q0 + j][d = 32 dt + 8 (r/4) + 4 hh + r%4]
     const float l_tot = l_run + __shfl_xor(l_run, 32);
@@ -399,12 +455,12 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
     if (item.slot < 0) {
         if (qrow < S) {
             const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-            const int64_t base = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+            const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
                 for (int g4 = 0; g4 < 4; ++g4)
-                    store4<OUT>(p.O, base + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
+                    store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
                                 o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
         }
     } else {
@@ -422,6 +478,8 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
             sc[128 * D + 128 + row] = l_tot;
         }
     }
+    STAMP(4);
+    }  // persistent loop over work items
 }
 
 // Merge the partial (O, m, l) of supertiles that were split along keys.  One workgroup per
@@ -625,6 +683,12 @@ smha_status_t upload_plan(smha_plan *p, int device_id) {
     bool ok = true;
     DeviceArrays &d = p->dev;
     p->device = device_id;
+    {
+        hipDeviceProp_t prop;
+        p->n_cu = hipGetDeviceProperties(&prop, device_id) == hipSuccess ? prop.multiProcessorCount : 256;
+        if (p->n_cu < 8) p->n_cu = 8;
+        p->n_cu = (p->n_cu + 7) / 8 * 8;
+    }
     if (p->has_row) {
         ok = ok && to_device(d.row_ptr, p->h_row_ptr) && to_device(d.col_idx, p->h_col_idx) &&
              to_device(d.col_off, p->h_col_off);
@@ -674,8 +738,10 @@ template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     const int BH = fp.B * fp.H;
     const int groups = (BH + 7) / 8;
-    const unsigned grid = (unsigned)(8 * groups * plan->max_items);
-    if (grid == 0) return hipSuccess;
+    fp.n_work = 8 * groups * plan->max_items;
+    if (fp.n_work == 0) return hipSuccess;
+    // two workgroups fit a CU (LDS at d = 128, registers at both head sizes)
+    const unsigned grid = (unsigned)std::min(fp.n_work, 2 * plan->n_cu);
     hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT>), dim3(grid), dim3(256), 0, stream, fp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -750,13 +816,14 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
     fp.items = dv.items; fp.item_off = dv.item_off; fp.item_cnt = dv.item_cnt; fp.max_items = plan->max_items;
-    fp.uent = dv.uent; fp.kt_bitmap = dv.kt_bitmap;
+    fp.uent = dv.uent; fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
     fp.max_slots = plan->max_slots;
     fp.split_rows = dv.split_rows; fp.split_off = dv.split_off; fp.split_cnt = dv.split_cnt;
     fp.row_ptr = dv.row_ptr; fp.col_idx = dv.col_idx; fp.col_off = dv.col_off;
 
 #ifdef SMHA_DEV
-    { const char *dbg = getenv("SMHA_DBG"); fp.dbg = dbg ? atoi(dbg) : 0; }
+    { const char *dbg = getenv("SMHA_DBG"); fp.dbg = dbg ? atoi(dbg) : 0;
+      const char *st = getenv("SMHA_STAMPS"); fp.stamps = st ? (unsigned long long *)strtoull(st, nullptr, 0) : nullptr; }
 #endif
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;

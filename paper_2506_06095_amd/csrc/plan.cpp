@@ -459,7 +459,7 @@ smha_status_t finish_plan(smha_plan *p) {
                 int64_t n_nonempty = 0;
                 for (int sp = 0; sp < nsup; ++sp) n_nonempty += sup_ptr[sp + 1] > sup_ptr[sp];
                 const double avg = n_nonempty ? (double)sup_ptr[nsup] / n_nonempty : 0.0;
-                const int chunk = std::max(16, (int)std::ceil(1.5 * avg));
+                const int chunk = std::min(64, std::max(16, (int)std::ceil(1.5 * avg)));  // the kernel holds one entry per lane
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
@@ -492,6 +492,7 @@ smha_status_t finish_plan(smha_plan *p) {
                 p->max_slots = std::max(p->max_slots, (int)slots);
             }
         }
+        if (p->has_block) p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), 64, 0ull);  // spare all-zero block
         // the per-row column list is large; drop it when no kernel will read it
         if (!p->has_row)
             for (auto &m : p->masks) {

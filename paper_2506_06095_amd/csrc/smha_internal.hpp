@@ -83,6 +83,7 @@ struct smha_plan {
     int max_items = 0, max_split_rows = 0, max_slots = 0;
 
     int device = -1;  // -1: nothing uploaded
+    int n_cu = 256;   // compute units of that device, rounded up to a multiple of 8
     smha::DeviceArrays dev;
 
     // scratch for split query tiles, grown on demand by smha_forward
