@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--kernel", choices=["auto", "row", "block"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = auto)")
+    ap.add_argument("--cold", action="store_true",
+                    help="rotate over enough Q/K/V/O sets that every step reads from HBM (not the headline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (outside the timed region) so that "
                          "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE can be scaled against known traffic")
@@ -66,6 +68,11 @@ def main() -> int:
     tdt = torch.float16 if c.dtype == "f16" else torch.bfloat16
     q, k, v = (torch.from_numpy(x.view(np.int16)).cuda().view(tdt) for x in (Q, K, V))
     out = torch.empty_like(q)
+    sets = [(q, k, v, out)]
+    if args.cold:  # working set well beyond the 256 MB Infinity Cache + L2
+        per_set = 4 * q.numel() * q.element_size()
+        for _ in range(max(2, int(1.5e9 // per_set))):
+            sets.append(tuple(t.clone() for t in (q, k, v, out)))
 
     force = {"auto": smha.SMHA_KERNEL_AUTO, "row": smha.SMHA_KERNEL_ROW, "block": smha.SMHA_KERNEL_BLOCK}[args.kernel]
     t0 = time.perf_counter()
@@ -85,14 +92,16 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        plan.forward(q, k, v, out=out)
+    for i in range(args.warmup):
+        a = sets[i % len(sets)]
+        plan.forward(a[0], a[1], a[2], out=a[3])
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     ev[0].record(stream)
     for i in range(args.steps):
-        plan.forward(q, k, v, out=out)
+        a = sets[(args.warmup + i) % len(sets)]
+        plan.forward(a[0], a[1], a[2], out=a[3])
         ev[i + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -128,7 +137,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": c.name, "B": B, "H": H, "S": S, "d": d, "block": c.block,
                    "kernel": kernel, "nnz_per_step": info["nnz"] * pairs_per_mask,
-                   "tiles64_per_step": info["n_tiles64"] * pairs_per_mask, "cache": "hot"},
+                   "tiles64_per_step": info["n_tiles64"] * pairs_per_mask,
+                   "cache": "cold (%d rotating sets)" % len(sets) if args.cold else "hot"},
         "latency_ms": {"mean": launch_ms, "median": float(np.median(per)), "min": float(per.min())},
         "tile_tflops": tile_flops / (launch_ms * 1e-3) / 1e12,
         "plan_ms": plan_ms,

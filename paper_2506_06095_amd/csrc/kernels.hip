@@ -121,9 +121,13 @@ __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dt
 //
 // K and V tiles go from global memory straight into LDS (buffer_load ... lds, 16 bytes per
 // lane, no registers and no vector-ALU work), both row-major [64 keys][D] with the 16-byte
-// chunks of a row XOR-swizzled by (row & 7) so that operand reads spread over the banks.  The
-// swizzle is applied on the global side: LDS chunk p of a row is filled with global chunk
-// p ^ (row & 7).  Rows past S read as zeros (buffer bounds), so ragged S needs no branches.
+// chunks of a row XOR-swizzled so that operand reads spread over the 64 banks (256 bytes):
+// a 16-byte K read is served 16 lanes (= 16 consecutive rows, one logical chunk) at a time, so
+// swz_k must be a bijection of those rows onto the 16 chunk slots of a 256-byte window; a
+// transposing V read is served 32 lanes at a time (4 consecutive rows x 4 consecutive chunks),
+// so swz_v must send those rows to different aligned groups of 4 chunks.  The swizzle is
+// applied on the global side: LDS chunk p of a row is filled with global chunk p ^ swz(row).
+// Rows past S read as zeros (buffer bounds), so ragged S needs no branches.
 // Both tiles are double-buffered: the loads of tile t+2 are issued right after the barrier
 // that ends tile t and are only waited for at the barrier that ends tile t+1.
 //
@@ -141,6 +145,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, in
 __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, int byte_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);  // out of range -> zeros
 }
+template <int D> __device__ __forceinline__ int swz_k(int row) { return (row / (128 / D)) & (D / 8 - 1); }
+template <int D> __device__ __forceinline__ int swz_v(int row) { return ((row / (128 / D)) & (D / 32 - 1)) << 2; }
 typedef __attribute__((address_space(3))) void lds_void;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -153,6 +159,21 @@ __device__ __forceinline__ void load_to_lds(__amdgpu_buffer_rsrc_t r, uint16_t *
 __device__ __forceinline__ u32x2 lds_read_tr(const uint16_t *src) {
     s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)src);
     return __builtin_bit_cast(u32x2, v);
+}
+
+// Read-only plan data at a wave-uniform address: through the constant address space, so the
+// load is a scalar one (a vector load would have to drain the wave's outstanding tile loads and
+// output stores before its value could be used).
+template <typename T>
+__device__ __forceinline__ T uniform_load(const T *ptr) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 16, "one or four dwords");
+    if constexpr (sizeof(T) == 4) {
+        typedef const uint32_t __attribute__((address_space(4))) *const_ptr;
+        return __builtin_bit_cast(T, *(const_ptr)(uintptr_t)ptr);
+    } else {
+        typedef const u32x4 __attribute__((address_space(4))) *const_ptr;
+        return __builtin_bit_cast(T, *(const_ptr)(uintptr_t)ptr);
+    }
 }
 
 template <int OUT>  // smha_dtype_t of the output
@@ -199,57 +220,132 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
     constexpr int OOB = 0x7FFFFF00;  // past every buffer: such loads return zeros without traffic
     const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    // LDS operand read offsets (elements).
-    // K fragment (kt, s): row 32 kt + j, logical chunk 2 s + hh -> physical (2s & 8) | ((2s & 7) ^ hh ^ (j & 7))
-    int k_rd[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) k_rd[c] = j * D + (((2 * c) ^ hh ^ (j & 7)) & 7) * 8;
-    // V^T fragment (dt, key group of 4): lane reads 8 bytes of row 4 hh' + (lane%16)/4 (hh' = lane/32),
-    // logical chunk 4 dt + 2 ((lane/16)&1) + (lane%4)/2, second half of the chunk if lane%4 is odd
+    // LDS operand read offsets (bytes inside a tile).
+    // K fragment (kt, s): row 32 kt + j, logical chunk 2 s + hh -> physical chunk (2 s) ^ hh ^ swz_k(j):
+    // byte offset k_rd ^ (32 s) (+ 64 kt D)
+    const int k_rd = j * D * 2 + ((hh ^ swz_k<D>(j)) * 16);
+    // V^T fragment (dt, key group of 4): lane reads 8 bytes of row 4 hh + (lane%16)/4 (+ 8 a + 16 cu),
+    // logical chunk 4 dt + 2 ((lane/16)&1) + (lane%4)/2, second half of the chunk if lane%4 is odd:
+    // byte offset v_rd ^ (64 dt) (+ 2 D (8 a + 16 cu))
     const int v_row = 4 * hh + ((lane & 15) >> 2);
-    int v_rd[2];
-#pragma unroll
-    for (int par = 0; par < 2; ++par)
-        v_rd[par] = v_row * D + (((4 * par + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) ^ v_row) & 7) * 8 + (lane & 1) * 4;
+    const int v_rd = v_row * D * 2 + ((swz_v<D>(v_row) + 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1)) * 16) + (lane & 1) * 8;
 
     // Persistent workgroups: the grid is a multiple of 8 that fills the chip once, and each
-    // workgroup walks the work list with that stride (so it stays on its XCD's heads); the
-    // output stores of one item drain while the next item starts.  Work index -> XCD = index
-    // mod 8 -> (batch*head) so that each XCD's L2 serves the K/V of one head at a time.
+    // workgroup walks the work list with that stride (so it stays on its XCD's heads).  Work
+    // index -> XCD = index mod 8 -> (batch*head), so that each XCD's L2 serves the K/V of one
+    // head at a time.  Items are software-pipelined: the next item's descriptor is fetched (scalar
+    // loads) while the current one starts; its entries, Q fragments and first K/V tile are
+    // requested right after the current item's last tile, before the current item's output
+    // stores, so memory latency of an item's start hides behind the previous item's end.
+    struct Work {  // wave-uniform
+        int valid, b, h, bh, qtile, begin, n, slot, col0, code0[2];  // col0, code0: the first entry
+    };
+    auto fetch_work = [&](int wg) __attribute__((always_inline)) {
+        Work wk;
+        const int xcd = wg & 7, rest = wg >> 3;
+        const int grp = rest / p.max_items, it = rest - grp * p.max_items;
+        wk.bh = grp * 8 + xcd;
+        wk.b = wk.bh / p.H;
+        wk.h = wk.bh - wk.b * p.H;
+        wk.valid = wg < p.n_work && wk.bh < p.B * p.H;
+        wk.qtile = wk.begin = wk.n = wk.col0 = 0;
+        wk.slot = -1;
+        wk.code0[0] = wk.code0[1] = -2;
+        if (wk.valid) {
+            const int mask = (p.Bm > 1 ? wk.b : 0) * p.Hm + (p.Hm > 1 ? wk.h : 0);
+            wk.valid = it < uniform_load(p.item_cnt + mask);
+            if (wk.valid) {
+                const Item item = uniform_load(p.items + uniform_load(p.item_off + mask) + it);
+                wk.qtile = item.qtile;
+                wk.begin = item.begin;
+                wk.n = item.end - item.begin;
+                wk.slot = item.slot;
+                const UEntry e0 = uniform_load(p.uent + item.begin);  // (the array ends with a spare entry)
+                wk.col0 = e0.col;
+                wk.code0[0] = wk.n > 0 ? e0.code[0] : -2;
+                wk.code0[1] = wk.n > 0 ? e0.code[1] : -2;
+            }
+        }
+        return wk;
+    };
+
+    const int ksb = (int)p.ks.s * 2, vsb = (int)p.vs.s * 2;  // row pitch in bytes
+    // global -> LDS: wave w fills the 1 KiB blocks w, w+4, ... of each tile; LDS chunk (row, pc)
+    // receives global chunk pc ^ swz(row).  Block w + 4 i starts 64 i / CPR * 4 rows (a multiple
+    // of 16) below block w, which leaves the swizzle alone: one per-lane offset serves all i.
+    constexpr int RSTEP = 4 * 64 / CPR;  // rows between two of a wave's blocks
+    int k_go, v_go;
+    {
+        const int pchunk = w * 64 + lane;
+        const int row = pchunk / CPR, pc = pchunk % CPR;
+        k_go = row * ksb + (pc ^ swz_k<D>(row)) * 16;
+        v_go = row * vsb + (pc ^ swz_v<D>(row)) * 16;
+    }
+
+    // state of the item being started / computed
+    __amdgpu_buffer_rsrc_t rK, rV;
+    // the item's entries, one per lane (at most 64, the planner cuts longer lists): requested
+    // here, not touched before the item's first wait
+    int raw_col = 0, raw_code0 = -2, raw_code1 = -2;
+    uint64_t raw_word = 0;  // bitmap word of the first tile (see fetch_word below)
+    // Each wave has a private quarter of the second buffer pair (free between items): its 32 Q rows
+    // are staged there (full-line requests instead of 32 partial lines per fragment load), and the
+    // binary16 / bfloat16 output tile is transposed there into whole rows before it is stored.
+    uint16_t *const priv = (w < 2 ? K1 : V1) + (w & 1) * (32 * D);
+    constexpr int NQL = CPR / 2;  // 1 KiB pieces of a 32-row slab
+    // Request everything an item needs before its first tile can be computed.
+    auto start_work = [&](const Work &wk) __attribute__((always_inline)) {
+        const __amdgpu_buffer_rsrc_t rQ = make_rsrc(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
+        rK = make_rsrc(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
+        rV = make_rsrc(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
+        {
+            const UEntry *u = p.uent + wk.begin + min(lane, max(wk.n - 1, 0));
+            raw_col = __builtin_nontemporal_load(&u->col);
+            raw_code0 = __builtin_nontemporal_load(&u->code[0]);
+            raw_code1 = __builtin_nontemporal_load(&u->code[1]);
+            const int c0 = (w >> 1) ? wk.code0[1] : wk.code0[0];
+            raw_word = p.kt_bitmap[(size_t)(c0 >= 0 ? c0 : p.bmp_spare) * 64 + 32 * (w & 1) + j];
+        }
+        // Q rows q0 .. q0+31 -> private slab, chunks swizzled like a K tile's (rows past S: zeros)
+        const int q0 = wk.qtile * 128 + 32 * w;
+        int lane_o = lane;
+        asm volatile("" : "+v"(lane_o));  // keeps the per-lane offsets below out of long-lived registers
+#pragma unroll
+        for (int i = 0; i < NQL; ++i) {
+            const int pchunk = i * 64 + lane_o;
+            const int row = pchunk / CPR, pc = pchunk % CPR;
+            load_to_lds(rQ, priv + i * 512, (q0 + row) * (int)p.qs.s * 2 + (pc ^ swz_k<D>(row)) * 16);
+        }
+        const int kb = wk.n > 0 ? wk.col0 * 64 * ksb : OOB, vb = wk.n > 0 ? wk.col0 * 64 * vsb : OOB;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            load_to_lds(rK, K0 + (w + 4 * i) * 512, k_go + (kb + i * RSTEP * ksb));
+            load_to_lds(rV, V0 + (w + 4 * i) * 512, v_go + (vb + i * RSTEP * vsb));
+        }
+    };
+    // Invariant at the top of the loop: everything requested for the item has landed (each way
+    // into the loop ends with the wait that makes it so, which lets the compiler see it too).
+    Work item = fetch_work(blockIdx.x);
+    if (item.valid) start_work(item);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     for (int wg = blockIdx.x; wg < p.n_work; wg += gridDim.x) {
     STAMP(0);
 #ifdef SMHA_DEV
     unsigned long long ph[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = 0;
 #endif
-    const int xcd = wg & 7, rest = wg >> 3;
-    const int grp = rest / p.max_items, it = rest - grp * p.max_items;
-    const int bh = grp * 8 + xcd;
-    if (bh >= p.B * p.H) continue;
-    const int b = bh / p.H, h = bh - b * p.H;
-    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
-    if (it >= p.item_cnt[mask]) continue;
-    const Item item = p.items[p.item_off[mask] + it];
-    const int n = item.end - item.begin;
-
-    const __amdgpu_buffer_rsrc_t rQ = make_rsrc(p.Q + b * p.qs.b + h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
-    const __amdgpu_buffer_rsrc_t rK = make_rsrc(p.K + b * p.ks.b + h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
-    const __amdgpu_buffer_rsrc_t rV = make_rsrc(p.V + b * p.vs.b + h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
-    const int ksb = (int)p.ks.s * 2, vsb = (int)p.vs.s * 2;  // row pitch in bytes
-
-    // Q^T operand: lane (j, hh) holds Q[q0 + j][16 s + 8 hh .. +8]; rows past S read as zeros
-    const int q0 = item.qtile * 128 + 32 * w;
-    u32x4 qf[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) qf[s] = buf_load16(rQ, (q0 + j) * (int)p.qs.s * 2 + (16 * s + 8 * hh) * 2);
-
-    // The item's entries (at most 64, the planner cuts longer lists) are fetched once, one per
-    // lane, and broadcast with readlane.
-    int e_col = 0, e_code = -2;
-    if (lane < n) {
-        const UEntry u = p.uent[item.begin + lane];
-        e_col = u.col;
-        e_code = u.code[w >> 1];
+    // the next item's descriptor: scalar loads that complete under this item's tiles
+    const Work nxt = fetch_work(wg + gridDim.x);
+    if (!item.valid) {  // (a hole in the work list: nothing was requested for it)
+        if (nxt.valid) start_work(nxt);
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        item = nxt;
+        continue;
     }
+    const int n = item.n;
+    const int b = item.b, h = item.h, bh = item.bh;
+    int e_col, e_code;
+    const int q0 = item.qtile * 128 + 32 * w;
+
     auto entry_col = [&](int t) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(e_col, t & 63); };
     auto entry_code = [&](int t) __attribute__((always_inline)) {
         return t < n ? __builtin_amdgcn_readlane(e_code, t & 63) : -2;
@@ -260,40 +356,41 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
         return p.kt_bitmap[(size_t)blk * 64 + 32 * (w & 1) + j];
     };
 
-    // global -> LDS: wave w fills the 1 KiB blocks w, w+4, ... of each tile; LDS chunk (row, pc)
-    // receives global chunk pc ^ (row & 7)
-    int k_go[LPW], v_go[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-        const int pchunk = (w + 4 * i) * 64 + lane;
-        const int row = pchunk / CPR, pc = pchunk % CPR;
-        k_go[i] = row * ksb + (pc ^ (row & 7)) * 16;
-        v_go[i] = row * vsb + (pc ^ (row & 7)) * 16;
-    }
-    auto load_tile = [&](int t, uint16_t *Kd, uint16_t *Vd) __attribute__((always_inline)) {  // past the end: zeros, no traffic
+    // the 2 LPW load instructions of one tile, addressable one at a time so that they can be
+    // slipped between MFMAs (a burst right after the barrier queues up behind the other waves'
+    // loads in the CU's one texture-address unit and blocks the wave for hundreds of cycles)
+    int ld_kb = OOB, ld_vb = OOB;
+    auto load_begin = [&](int t) __attribute__((always_inline)) {  // past the end: zeros, no traffic
         const int col = entry_col(t);
-        const int kb = t < n ? col * 64 * ksb : OOB, vb = t < n ? col * 64 * vsb : OOB;
-#pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            load_to_lds(rK, Kd + (w + 4 * i) * 512, k_go[i] + kb);
-            load_to_lds(rV, Vd + (w + 4 * i) * 512, v_go[i] + vb);
-        }
+        ld_kb = t < n ? col * 64 * ksb : OOB;
+        ld_vb = t < n ? col * 64 * vsb : OOB;
+    };
+    auto load_piece = [&](int i, uint16_t *Kd, uint16_t *Vd) __attribute__((always_inline)) {  // i in [0, 2 LPW)
+        if (i & 1)
+            load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 512, v_go + (ld_vb + (i >> 1) * RSTEP * vsb));
+        else
+            load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 512, k_go + (ld_kb + (i >> 1) * RSTEP * ksb));
     };
 
+    u32x4 qf[NS];  // Q^T operand: lane (j, hh) holds Q[q0 + j][16 s + 8 hh .. +8], read from the slab below
     float m_run = NEG_INF, l_run = 0.f;
     f32x16 o[NDT];
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt) o[dt] = zero16;
 
     // one tile for this wave
-    auto compute_tile = [&](const uint16_t *kp, const uint16_t *vp, int code, uint64_t word) __attribute__((always_inline)) {
-        if (code >= 0 && __builtin_amdgcn_ballot_w64(word != 0) == 0) return;  // nothing for these 32 rows
+    auto compute_tile = [&](const uint16_t *kp, const uint16_t *vp, uint16_t *Kn, uint16_t *Vn, int code, uint64_t word) __attribute__((always_inline)) {
+        if (code >= 0 && __builtin_amdgcn_ballot_w64(word != 0) == 0) {  // nothing for these 32 rows
+#pragma unroll
+            for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
+            return;
+        }
         // scores, transposed: acc[kt][r] = S[q = j][key = 32 kt + 8 (r/4) + 4 hh + r%4].
         // Fragments are requested PF MFMAs ahead of their use (LDS latency is several MFMAs).
         f32x16 acc[2] = {zero16, zero16};
         auto k_addr = [&](int i) __attribute__((always_inline)) {  // i = 2 s + kt
             const int s = i >> 1, kt = i & 1;
-            return kp + k_rd[s & 3] + 32 * kt * D + ((2 * s) & 8) * 8;
+            return reinterpret_cast<const char *>(kp) + ((k_rd ^ (32 * s)) + 64 * kt * D);
         };
         u32x4 kfrag[PF];
 #pragma unroll
@@ -303,6 +400,7 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
         for (int i = 0; i < 2 * NS; ++i) {  // the two accumulator chains alternate
             acc[i & 1] = mfma32<BF16>(kfrag[i % PF], qf[i >> 1], acc[i & 1]);
             if (i + PF < 2 * NS) kfrag[i % PF] = *reinterpret_cast<const u32x4 *>(k_addr(i + PF));
+            if ((i & 1) == 0) load_piece(i >> 1, Kn, Vn);  // next tile's loads ride under the MFMAs (2 NS = 4 LPW)
             __builtin_amdgcn_sched_barrier(0);
         }
         PHASE(2);
@@ -366,8 +464,8 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
         // group cu+1 are issued between the MFMAs of group cu, so they run under the matrix pipe.
         auto v_frag = [&](int i) __attribute__((always_inline)) {  // i = cu * NDT + dt
             const int cu = i / NDT, dt = i % NDT;
-            const uint16_t *ptr = vp + v_rd[dt & 1] + (16 * cu) * D + ((4 * dt) & 8) * 8;
-            const u32x2 lo = lds_read_tr(ptr), hi = lds_read_tr(ptr + 8 * D);
+            const char *ptr = reinterpret_cast<const char *>(vp) + ((v_rd ^ (64 * dt)) + 32 * cu * D);
+            const u32x2 lo = lds_read_tr(reinterpret_cast<const uint16_t *>(ptr)), hi = lds_read_tr(reinterpret_cast<const uint16_t *>(ptr + 16 * D));
             return u32x4{lo[0], lo[1], hi[0], hi[1]};
         };
         u32x4 vfrag[PF];
@@ -404,80 +502,129 @@ __global__ void __launch_bounds__(256, 2) smha_block_fwd(const FwdParams p) {
         l_run += psum;
     };
 
-    // ---- main loop: tile t from LDS buffer t&1 while tile t+1 lands in the other buffer; the
-    // loads of tile t+2 are issued as soon as every wave has finished with tile t.  Unrolled by
-    // two so that each buffer is a compile-time object.
+    // ---- main loop: tile t is computed from one LDS buffer while the loads of tile t+1 are
+    // issued (between the MFMAs) into the other, which every wave left at the previous barrier;
+    // they are waited for at the barrier that ends tile t.  Unrolled by two so that each buffer
+    // is a compile-time object.
     STAMP(1);
-    int code = entry_code(0);
-    uint64_t word = fetch_word(code);
-    if (n > 0) {
-        load_tile(0, K0, V0);
-        __builtin_amdgcn_s_waitcnt(0x0070);  // tile 0 landed (also Q, entries, first bitmap word)
-        __builtin_amdgcn_s_barrier();
-        load_tile(1, K1, V1);
+    e_col = raw_col;
+    e_code = lane < n ? ((w >> 1) ? raw_code1 : raw_code0) : -2;
+    {
+        int krd = k_rd;
+        asm volatile("" : "+v"(krd));  // (the fragment addresses are made here, not kept across items)
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            qf[s] = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(priv) + (krd ^ (32 * s)));
     }
+    int code = entry_code(0);
+    uint64_t word = raw_word;
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the slab is read before tile 1 may overwrite it
+    __builtin_amdgcn_s_barrier();        // every wave's part of tile 0 is visible
     STAMP(2);
 #ifdef SMHA_DEV
     if (p.dbg & 256) tprev = __builtin_readcyclecounter();
 #endif
-    auto step = [&](int t, uint16_t *Kc, uint16_t *Vc) __attribute__((always_inline)) {
+    auto step = [&](int t, uint16_t *Kc, uint16_t *Vc, uint16_t *Kn, uint16_t *Vn) __attribute__((always_inline)) {
         const int code_next = entry_code(t + 1);
         const uint64_t word_next = fetch_word(code_next);
+        load_begin(t + 1);
         PHASE(0);
-        if (code != -2) compute_tile(Kc, Vc, code, word);
+        if (code != -2) {
+            compute_tile(Kc, Vc, Kn, Vn, code, word);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
+        }
         PHASE(4);
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tile t+1 landed, own LDS reads done
         PHASE(6);
         __builtin_amdgcn_s_barrier();        // ... for every wave: tile t+1 visible, tile t free
         PHASE(5);
-        load_tile(t + 2, Kc, Vc);
-        PHASE(1);
         code = code_next;
         word = word_next;
     };
     for (int t = 0; t < n; t += 2) {
-        step(t, K0, V0);
-        if (t + 1 < n) step(t + 1, K1, V1);
+        step(t, K0, V0, K1, V1);
+        if (t + 1 < n) step(t + 1, K1, V1, K0, V0);
     }
 
     STAMP(3);
 #ifdef SMHA_DEV
     if ((p.dbg & 256) && p.stamps && threadIdx.x == 0) { p.stamps[(size_t)wg * 8 + 5] = ph[0] + (ph[1] << 32); p.stamps[(size_t)wg * 8 + 6] = ph[2] + (ph[3] << 32); p.stamps[(size_t)wg * 8 + 7] = ph[4] + (ph[5] << 32); p.stamps[(size_t)wg * 8 + 1] = ph[6]; }
 #endif
-    // the loads of tiles n, n+1 (zeros) were issued into both buffers: let them land before the
-    // next item overwrites the buffers (before the output stores, which may then drain freely)
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    __builtin_amdgcn_s_barrier();
-
+    // Every load issued for this item has landed and every wave is past its last LDS read (the
+    // last barrier), so the next item's requests can go out now; the output stores follow them.
     // o[dt][r] = O[q = q0 + j][d = 32 dt + 8 (r/4) + 4 hh + r%4]
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const int qrow = q0 + j;
-    if (item.slot < 0) {
-        if (qrow < S) {
-            const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-            const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
-#pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4)
-                    store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
-                                o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
-        }
-    } else {
-        float *sc = p.scratch + ((size_t)bh * p.max_slots + item.slot) * (size_t)(128 * D + 256);
-        const int row = 32 * w + j;
+    if (item.slot < 0 && OUT != SMHA_F32) {
+        // 16-bit output: the wave's 32 x D tile goes through its private LDS slab (chunk-swizzled
+        // rows) and leaves as whole rows, 16 bytes per lane
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));  // (addresses below are made here, not kept in registers across the item)
+        const int je = lane_e & 31, he = lane_e >> 5;
+        const int o_wr = je * D * 2 + swz_k<D>(je) * 16 + he * 8;
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
-                *reinterpret_cast<f32x4 *>(sc + row * D + 32 * dt + 8 * g4 + 4 * hh) = v;
+                const u32x2 v = {pack2<OUT == SMHA_BF16>(o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv),
+                                 pack2<OUT == SMHA_BF16>(o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv)};
+                *reinterpret_cast<u32x2 *>(reinterpret_cast<char *>(priv) + (o_wr ^ ((4 * dt + g4) * 16))) = v;
+                __builtin_amdgcn_sched_barrier(0);  // (pack and write as we go: no second copy of the tile in registers)
             }
-        if (hh == 0) {
-            sc[128 * D + row] = m_run * p.c;  // -inf stays -inf (c > 0)
-            sc[128 * D + 128 + row] = l_tot;
+        u32x4 ov[NQL];
+#pragma unroll
+        for (int i = 0; i < NQL; ++i) ov[i] = *reinterpret_cast<const u32x4 *>(priv + (i * 64 + lane_e) * 8);
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the slab is read before the next Q may land in it
+        if (nxt.valid) start_work(nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        // NQL stores, every one issued by every wave (rows past S fall outside the buffer and are
+        // dropped), so that the wait below can count them
+        const __amdgpu_buffer_rsrc_t rO = make_rsrc(reinterpret_cast<const uint16_t *>(p.O) + b * p.os.b + h * p.os.h,
+                                                    ((int64_t)(S - 1) * p.os.s + D) * 2);
+#pragma unroll
+        for (int i = 0; i < NQL; ++i) {
+            const int pchunk = i * 64 + lane_e;
+            const int row = pchunk / CPR, pc = pchunk % CPR;
+            __builtin_amdgcn_raw_buffer_store_b128(ov[i], rO, (q0 + row) * (int)p.os.s * 2 + (pc ^ swz_k<D>(row)) * 16, 0, 0);
         }
+        // The next item's requests were issued before these stores and memory operations retire
+        // in order: allowing NQL operations to stay outstanding waits for the requests only.
+        __builtin_amdgcn_s_waitcnt(0x0070 | (NQL & 15) | ((NQL >> 4) << 14));  // vmcnt(NQL) lgkmcnt(0)
+    } else {
+        if (nxt.valid) start_work(nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        if (item.slot < 0) {
+            if (qrow < S) {
+                const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+                const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+#pragma unroll
+                for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4)
+                        store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
+                                    o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
+            }
+        } else {
+            float *sc = p.scratch + ((size_t)bh * p.max_slots + item.slot) * (size_t)(128 * D + 256);
+            const int row = 32 * w + j;
+#pragma unroll
+            for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
+                    *reinterpret_cast<f32x4 *>(sc + row * D + 32 * dt + 8 * g4 + 4 * hh) = v;
+                }
+            if (hh == 0) {
+                sc[128 * D + row] = m_run * p.c;  // -inf stays -inf (c > 0)
+                sc[128 * D + 128 + row] = l_tot;
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     }
+    item = nxt;
     STAMP(4);
     }  // persistent loop over work items
 }
@@ -786,11 +933,15 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     const uintptr_t align = (uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O;
     if (align & 15) return SMHA_ERR_UNSUPPORTED;
     if ((int64_t)B * H > (1 << 24)) return SMHA_ERR_UNSUPPORTED;
-    {   // the block kernel addresses one head's Q/K/V through 32-bit buffer offsets
+    {   // the block kernel addresses one head's Q/K/V/O through 32-bit buffer offsets
         const int64_t lim = (int64_t)1 << 31;
         const int64_t rows = (int64_t)plan->S + 128;
         const int64_t qs = q_strides ? q_strides[2] : d, ks = k_strides ? k_strides[2] : d, vs = v_strides ? v_strides[2] : d;
-        if ((rows * qs + d) * 2 >= lim || (rows * ks + d) * 2 >= lim || (rows * vs + d) * 2 >= lim) return SMHA_ERR_UNSUPPORTED;
+        const int64_t os = o_strides ? o_strides[2] : d;
+        if (qs < d || ks < d || vs < d || os < d) return SMHA_ERR_UNSUPPORTED;  // rows must not overlap
+        if ((rows * qs + d) * 2 >= lim || (rows * ks + d) * 2 >= lim || (rows * vs + d) * 2 >= lim ||
+            (rows * os + d) * 2 >= lim)
+            return SMHA_ERR_UNSUPPORTED;
     }
     int which = kernel == SMHA_KERNEL_AUTO ? plan->kernel : (int)kernel;
     if (which == SMHA_KERNEL_ROW && !plan->has_row) return SMHA_ERR_UNSUPPORTED;

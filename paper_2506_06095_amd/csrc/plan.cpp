@@ -374,15 +374,19 @@ static double eq1_threshold(double valid16, int S) {
     return valid16 / (n * n) - 1.2 / (lg * lg);
 }
 
-// Cost-model constants in nanoseconds, per (batch, head) pair on a busy MI355X.
+// Cost-model constants in nanoseconds of whole-chip time per (batch, head) pair, from MI355X
+// timings of both kernels with many pairs in flight:
+//   block kernel: 158 us / (32 pairs * 1249 tiles) = 4.0 ns per tile at d = 128 (BigBird, S 8192),
+//                 68 us / (64 pairs * 318 tiles) = 3.4 ns per tile at d = 64 (strided causal, S 2048);
+//   row kernel:   232 us / (64 pairs * 269376 entries) = 0.0134 ns per entry at d = 64,
+//                 3.24 ms / (32 pairs * 5.08 M entries) = 0.020 ns per entry at d = 128, and about
+//                 0.4 ns per query row of fixed cost (scattered mask, 9 entries per row: 68 us).
 struct CostModel {
     double tile_ns, entry_ns, row_ns;
 };
 static CostModel cost_model(int d) {
-    // t_tile: one 64x64 tile of the block kernel; t_entry: one unmasked entry of the row
-    // kernel (a K row and a V row gathered through L2); t_row: fixed cost per query row.
-    if (d == 128) return {0.70, 0.014, 0.020};
-    return {0.45, 0.008, 0.015};
+    if (d == 128) return {4.0, 0.020, 0.5};
+    return {3.4, 0.0134, 0.4};
 }
 
 smha_status_t finish_plan(smha_plan *p) {
@@ -492,7 +496,10 @@ smha_status_t finish_plan(smha_plan *p) {
                 p->max_slots = std::max(p->max_slots, (int)slots);
             }
         }
-        if (p->has_block) p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), 64, 0ull);  // spare all-zero block
+        if (p->has_block) {
+            p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), 64, 0ull);  // spare all-zero block
+            p->h_uent.push_back(UEntry{0, {-2, -2}, 0});             // spare entry: an empty item may read one past its list
+        }
         // the per-row column list is large; drop it when no kernel will read it
         if (!p->has_row)
             for (auto &m : p->masks) {
@@ -612,7 +619,7 @@ extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *
         i.n_valid16 += m.n_valid16;
         i.n_tiles64 += (int64_t)m.kt_col.size();
     }
-    i.n_union = (int64_t)p->h_uent.size();
+    i.n_union = p->h_uent.empty() ? 0 : (int64_t)p->h_uent.size() - 1;  // (without the spare entry)
     i.n_items = (int64_t)p->h_items.size();
     i.n_split_rows = (int64_t)p->h_split_rows.size();
     i.eq1_threshold = p->eq1_threshold;
