@@ -162,8 +162,9 @@ smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_exp
  *   Q, K, V         device, [B][H][S][d] of in_dtype, addressed through *_strides
  *   O               device, [B][H][S][d] of out_dtype (same as in_dtype, or SMHA_F32)
  *   *_strides       host, {batch, head, seq} strides in elements, d is contiguous;
- *                   NULL = packed.  Pointers must be 16-byte aligned and strides multiples
- *                   of 8 elements (UNSUPPORTED otherwise).
+ *                   NULL = packed.  Pointers must be 16-byte aligned, strides multiples of
+ *                   8 elements, the seq stride at least d, and one (batch, head) slice of
+ *                   each tensor must span less than 2 GiB (UNSUPPORTED otherwise).
  *   scale           <= 0 selects 1/sqrt(d)
  *   kernel          AUTO = the plan's choice; ROW/BLOCK need that format in the plan
  * The plan is read-only here except for a scratch buffer the block kernel uses when a
