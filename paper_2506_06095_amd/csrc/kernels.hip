@@ -413,12 +413,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
                     if (!((bits >> (8 * (r / 4) + (r % 4))) & 1u)) acc[kt][r] = NEG_INF;
             }
         }
-        // Probabilities against the current reference, optimistically: the row maximum is not
-        // needed unless some probability would exceed 2^8, and that shows in the row sum that is
-        // formed anyway.  Only then (always on an item's first tile, rarely afterwards) is the
-        // reference raised, O and l rescaled, and the key group redone.
+        // Lazily raised reference: probabilities are formed against the running reference m_run
+        // as long as no score of the tile exceeds it by more than 8 / c (they then stay below 2^8:
+        // safe in binary16, exact enough in the fp32 sums).  One test per tile, on the raw scores
+        // (a test on the exponentials' sums, per key group, costs nothing in instructions but makes
+        // every group's MFMAs wait for a branch on the last exponential: measured 330 instead of
+        // 160 cycles per group).  Only when the test fires (always on an item's first tile, rarely
+        // afterwards) is the reference raised to the tile's maximum and O and l rescaled.
         float mc = (m_run == NEG_INF ? 0.f : m_run) * p.c;
-        float psum = 0.f;
         u32x4 pf[4][NP];  // [cu = 2 kt + u: keys 16 cu .. 16 cu + 15][hi/lo]
         auto p_pair = [&](int cu, int q, float &gs) __attribute__((always_inline)) {  // pair q (0..3) of key group cu
             const int kt = cu >> 1, u = cu & 1;
@@ -440,12 +442,13 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
                 gs = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, packed), __builtin_bit_cast(h2, 0x3C003C00u), gs, false);
             }
         };
-        auto raise_reference = [&]() __attribute__((always_inline)) {
-            float mt = NEG_INF;
+        float mt = NEG_INF;  // this lane's 32 of the row's 64 scores
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mt = fmaxf(mt, acc[kt][r]);
+            for (int r = 0; r < 16; ++r) mt = fmaxf(mt, acc[kt][r]);
+        // (m_run = -inf: any finite score fires; a row with nothing but masked keys never does)
+        if (__builtin_amdgcn_ballot_w64(mt > m_run + thr_raw) != 0) {
             mt = fmaxf(mt, __shfl_xor(mt, 32));
             const float m_new = fmaxf(m_run, mt);
             const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
@@ -453,12 +456,9 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
             m_run = m_new;
             mc = m_use * p.c;
             l_run *= alpha;
-            psum *= alpha;
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-        };
+            for (int dt = 0; dt < NDT; ++dt) o[dt] *= alpha;
+        }
         // O^T += V^T P^T.  Fragment (cu, dt): keys 16 cu + 8 a + 4 hh + 0..3 (a = 0, 1) of columns
         // 32 dt + j: two transposing reads, requested PF MFMAs ahead.  The exponentials of key
         // group cu+1 are issued between the MFMAs of group cu, so they run under the matrix pipe.
@@ -474,18 +474,10 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         float gs = 0.f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) p_pair(0, q, gs);
+        PHASE(1);
 #pragma unroll
         for (int cu = 0; cu < 4; ++cu) {
-            // (a row without a reference yet must get one before anything is accumulated for it)
-            if (__builtin_amdgcn_ballot_w64(!(gs <= 256.f) || m_run == NEG_INF) != 0) {
-                raise_reference();
-                gs = 0.f;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) p_pair(cu, q, gs);
-            }
-            psum += gs;
-            gs = 0.f;
-            __builtin_amdgcn_sched_barrier(0);
+            if (cu == 1) PHASE(3);
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
                 const int i = cu * NDT + dt;
@@ -499,7 +491,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        l_run += psum;
+        l_run += gs;
     };
 
     // ---- main loop: tile t is computed from one LDS buffer while the loads of tile t+1 are
@@ -888,7 +880,10 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     fp.n_work = 8 * groups * plan->max_items;
     if (fp.n_work == 0) return hipSuccess;
     // two workgroups fit a CU (LDS at d = 128, registers at both head sizes)
-    const unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 3 : 2) * plan->n_cu);
+    unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 3 : 2) * plan->n_cu);
+#ifdef SMHA_DEV
+    if (const char *g = getenv("SMHA_GRID")) grid = (unsigned)atoi(g);
+#endif
     hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT>), dim3(grid), dim3(256), 0, stream, fp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

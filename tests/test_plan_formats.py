@@ -165,6 +165,18 @@ def test_error_paths_return_status_codes():
                                 None, None, None, None, 0.0, 0, None) == 2
         assert lib.smha_forward(ctypes.c_void_p(p.handle), None, addr, addr, addr, 1, 1, 64, 0, 0,
                                 None, None, None, None, 0.0, 0, None) == 1
+        # strides: rows that overlap (seq stride < d), a stride that is not a multiple of 8, and a
+        # (batch, head) slice beyond the 2 GiB the kernels address with 32-bit offsets
+        I3 = ctypes.c_int64 * 3
+        ok = I3(8 * 64, 8 * 64, 64)
+        for bad in (I3(8 * 64, 8 * 64, 32), I3(8 * 64, 8 * 64, 68), I3(1 << 40, 1 << 34, 1 << 28)):
+            for pos in range(4):
+                strides = [ok, ok, ok, ok]
+                strides[pos] = bad
+                assert lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 64, 0, 0,
+                                        *strides, 0.0, 0, None) == 2
+        assert lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 64, 0, 0,
+                                ok, ok, ok, ok, 0.0, 0, None) == 5
     with smha.Plan.from_dense(np.ones((2, 3, 8, 8), np.uint8), device_id=-2) as p:
         st = lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 4, 3, 64, 0, 0,
                               None, None, None, None, 0.0, 0, None)
