@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = auto)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over enough Q/K/V/O sets that every step reads from HBM (not the headline)")
+    ap.add_argument("--dense-device-mask", action="store_true",
+                    help="build the plan from a dense byte mask that lives in device memory (packed to bits by "
+                         "the GPU) instead of from the pattern description; plan_ms then covers that path")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (outside the timed region) so that "
                          "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE can be scaled against known traffic")
@@ -77,9 +80,19 @@ def main() -> int:
             sets.append(tuple(t.clone() for t in (q, k, v, out)))
 
     force = {"auto": smha.SMHA_KERNEL_AUTO, "row": smha.SMHA_KERNEL_ROW, "block": smha.SMHA_KERNEL_BLOCK}[args.kernel]
-    t0 = time.perf_counter()
-    plan = smha.Plan.from_desc(c.mask, B, H, S, block=c.block, head_dim=d, force=force)
-    plan_ms = (time.perf_counter() - t0) * 1e3
+    if args.dense_device_mask:
+        dense = W.dense_mask(c.mask, B, H, S)
+        dev_mask = torch.from_numpy(dense).cuda()
+        smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force).close()   # warm-up (first launch)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plan = smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force)
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        del dev_mask, dense
+    else:
+        t0 = time.perf_counter()
+        plan = smha.Plan.from_desc(c.mask, B, H, S, block=c.block, head_dim=d, force=force)
+        plan_ms = (time.perf_counter() - t0) * 1e3
     info = plan.info()
     n_masks = info["Bm"] * info["Hm"]
     pairs_per_mask = B * H // n_masks
@@ -140,6 +153,7 @@ def main() -> int:
         "config": {"workload": c.name, "B": B, "H": H, "S": S, "d": d, "block": c.block,
                    "kernel": kernel, "nnz_per_step": info["nnz"] * pairs_per_mask,
                    "tiles64_per_step": info["n_tiles64"] * pairs_per_mask,
+                   "plan_from": "dense device mask" if args.dense_device_mask else "pattern description",
                    "cache": "cold (%d rotating sets)" % len(sets) if args.cold else "hot"},
         "latency_ms": {"mean": launch_ms, "median": float(np.median(per)), "min": float(per.min())},
         "tile_tflops": tile_flops / (launch_ms * 1e-3) / 1e12,

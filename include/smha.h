@@ -134,8 +134,10 @@ typedef enum {
 
 /* Mask analysis (Sec. 4.2.1) from a dense boolean mask.
  *   mask            uint8 [Bm][Hm][S][S], nonzero = attend; host pointer if mask_on_device
- *                   is 0, else a device pointer on the current device (the scan then runs
- *                   on the GPU; the call synchronises before returning)
+ *                   is 0, else a device pointer on the current device (the mask is then
+ *                   packed to bit rows by a GPU kernel on the default stream and only those
+ *                   cross to the host, where the formats are built; the call synchronises
+ *                   before returning)
  *   opts            may be NULL (defaults)
  *   out             receives the plan
  * Errors: INVALID_ARG (null, Bm/Hm/S < 1), UNSUPPORTED (block), ALLOC, HIP. */

@@ -790,8 +790,54 @@ int current_device_or_negative() {
     return dev;
 }
 
-smha_status_t copy_mask_to_host(const uint8_t *dev_mask, size_t bytes, uint8_t *host_dst) {
-    if (hipMemcpy(host_dst, dev_mask, bytes, hipMemcpyDeviceToHost) != hipSuccess) {
+// Mask intake on the device (Sec. 4.2.1: the mask is analysed once): a dense byte mask is
+// packed into bit rows, one thread per 64-bit word = 64 mask bytes, so that only S*S/8 bytes
+// cross to the host for the format analysis.  HBM-bound: S*S bytes read, S*S/8 written per mask.
+// words[(mask*S + i) * W + t] bit c = (mask[i][64 t + c] != 0), entries past S are 0.
+__global__ void __launch_bounds__(256) smha_mask_pack_bits(const uint8_t *__restrict__ mask, uint64_t *__restrict__ words,
+                                                           int S, int W, long long n_words) {
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_words) return;
+    const long long row = g / W;  // mask * S + i
+    const int t = (int)(g - row * W);
+    const uint8_t *src = mask + row * S + 64 * (long long)t;
+    const int n = min(64, S - 64 * t);
+    uint64_t out = 0;
+    if (n == 64 && ((uintptr_t)src & 15) == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u32x4 v = reinterpret_cast<const u32x4 *>(src)[q];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                // any nonzero byte -> its bit 0, then gather the four bit-0s of the dword
+                uint32_t x = v[e];
+                x |= x >> 4;
+                x |= x >> 2;
+                x |= x >> 1;
+                x &= 0x01010101u;
+                out |= (uint64_t)((x * 0x10204080u) >> 28) << (16 * q + 4 * e);
+            }
+        }
+    } else {
+        for (int c = 0; c < n; ++c) out |= (uint64_t)(src[c] != 0) << c;
+    }
+    words[g] = out;
+}
+
+smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int S, uint64_t *host_words) {
+    const int W = (S + 63) / 64;
+    const long long n_words = (long long)n_masks * S * W;
+    uint64_t *d_words = nullptr;
+    if (hipMalloc(reinterpret_cast<void **>(&d_words), (size_t)n_words * 8) != hipSuccess) {
+        (void)hipGetLastError();
+        return SMHA_ERR_ALLOC;
+    }
+    const unsigned grid = (unsigned)((n_words + 255) / 256);
+    hipLaunchKernelGGL(smha_mask_pack_bits, dim3(grid), dim3(256), 0, 0, dev_mask, d_words, S, W, n_words);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(host_words, d_words, (size_t)n_words * 8, hipMemcpyDeviceToHost);
+    (void)hipFree(d_words);
+    if (e != hipSuccess) {
         (void)hipGetLastError();
         return SMHA_ERR_HIP;
     }

@@ -78,6 +78,14 @@ struct DenseSource final : RowSource {
     }
 };
 
+// bit rows that were packed elsewhere (on the GPU, for a device mask)
+struct BitSource final : RowSource {
+    const uint64_t *w;
+    int W;
+    BitSource(const uint64_t *words, int S_) : w(words), W((S_ + 63) / 64) {}
+    void row_bits(int i, uint64_t *words) const override { std::memcpy(words, w + (size_t)i * W, sizeof(uint64_t) * W); }
+};
+
 inline uint64_t mix64(uint64_t x) {  // splitmix64 output function
     x += 0x9E3779B97F4A7C15ull;
     uint64_t z = x;
@@ -535,18 +543,22 @@ extern "C" smha_status_t smha_plan_from_dense(const uint8_t *mask, int mask_on_d
         std::unique_ptr<smha_plan> p(new smha_plan);
         p->S = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
         const size_t per_mask = (size_t)S * S;
-        std::vector<uint8_t> staged;
-        const uint8_t *host = mask;
+        const size_t words_per_mask = (size_t)S * ((S + 63) / 64);
+        std::vector<uint64_t> packed;  // a device mask is packed to bits on the GPU: 1/8 of the bytes cross over
         if (mask_on_device) {
-            staged.resize(per_mask * Bm * Hm);
-            st = copy_mask_to_host(mask, staged.size(), staged.data());
+            packed.resize(words_per_mask * Bm * Hm);
+            st = pack_device_mask(mask, Bm * Hm, S, packed.data());
             if (st != SMHA_OK) return st;
-            host = staged.data();
         }
         p->masks.resize((size_t)Bm * Hm);
         for (int mi = 0; mi < Bm * Hm; ++mi) {
-            DenseSource src(host + per_mask * mi, S);
-            st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+            if (mask_on_device) {
+                BitSource src(packed.data() + words_per_mask * mi, S);
+                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+            } else {
+                DenseSource src(mask + per_mask * mi, S);
+                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+            }
             if (st != SMHA_OK) return st;
         }
         st = finish_plan(p.get());

@@ -99,7 +99,8 @@ smha_status_t finish_plan(smha_plan *p);      // selector, work lists, concatena
 // device.hip
 smha_status_t upload_plan(smha_plan *p, int device_id);
 void release_device(smha_plan *p);
-smha_status_t copy_mask_to_host(const uint8_t *dev_mask, size_t bytes, uint8_t *host_dst);
+// device byte masks [n_masks][S][S] -> host bit rows [n_masks][S][ceil(S/64)] (packed on the GPU)
+smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int S, uint64_t *host_words);
 int current_device_or_negative();
 
 }  // namespace smha

@@ -199,6 +199,29 @@ def test_strided_tensors_device_mask_and_determinism(torch_mod, smha):
         check(out3.float().cpu().numpy(), ref, "side stream")
 
 
+@pytest.mark.parametrize("S", [1, 63, 100, 130, 512, 1000])
+def test_device_mask_is_packed_on_the_gpu_and_gives_the_host_plan(torch_mod, smha, S):
+    """A mask that lives in device memory goes through the bit-packing kernel; every index array of
+    the plan must equal, bit for bit, the one built from the same mask in host memory (and through
+    it the format oracle, which the host path is tested against).  Any nonzero byte means attend."""
+    torch = torch_mod
+    rng = np.random.default_rng(S)
+    masks = (rng.random((2, 3, S, S)) < 0.3).astype(np.uint8)
+    masks[masks != 0] = rng.integers(1, 256, size=int(masks.sum()), dtype=np.uint8)   # 1..255, not just 1
+    masks[1, 2] = 0                                                                    # an empty mask
+    masks[0, 1, :, : min(S, 70)] = 255                                                 # full tiles
+    dev = torch.from_numpy(masks).cuda()
+    for bs in (16, 64):
+        with smha.Plan.from_dense(masks, block=bs, build_both=True) as ph, \
+                smha.Plan.from_dense(dev, block=bs, build_both=True) as pd:
+            ih, idv = ph.info(), pd.info()
+            for key in ("nnz", "n_valid", "n_full", "n_part", "n_valid16", "n_tiles64", "n_union", "n_items", "kernel"):
+                assert ih[key] == idv[key], key
+            for mi in range(6):
+                for which in ("row_ptr", "col_idx", "load_row_ptr", "load_col_idx", "flags", "bitmap"):
+                    np.testing.assert_array_equal(ph.export(which, mi), pd.export(which, mi), err_msg=f"{which} mask {mi} bs {bs}")
+
+
 def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
     """Scattered mask -> the calibrated selector picks row-wise and it is not slower than the
     block kernel there; block-structured mask -> the reverse."""
