@@ -151,9 +151,21 @@ typedef __attribute__((address_space(3))) void lds_void;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-// 64 lanes x 16 bytes from per-lane global offsets into 1 KiB of LDS at `dst` (lane l -> dst + 16 l)
-__device__ __forceinline__ void load_to_lds(__amdgpu_buffer_rsrc_t r, uint16_t *dst, int byte_off) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void *)dst, 16, byte_off, 0, 0, 0);
+// Buffer descriptor as four dwords (base, no stride, size in bytes, raw 32-bit data format) for the
+// loads below; out-of-range offsets return zeros.
+__device__ __forceinline__ u32x4 make_rsrc4(const void *base, int64_t bytes) {
+    const uint64_t a = (uint64_t)base;
+    return u32x4{(uint32_t)a, (uint32_t)(a >> 32) & 0xFFFFu, (uint32_t)bytes, 0x00020000u};
+}
+// 64 lanes x 16 bytes from per-lane global offsets into 1 KiB of LDS at byte address `lds`
+// (lane l -> lds + 16 l), bypassing registers.  Written as an instruction: the compiler's own
+// form makes it track which LDS object each load in flight may write, which forces the two
+// buffers of a pair to be compile-time objects (a loop body per buffer) and adds full waits
+// wherever it cannot tell; here every wait for these loads is an explicit s_waitcnt in the
+// kernel (memory operations retire in order, so the compiler's own vmcnt waits stay safe).
+__device__ __forceinline__ void load_to_lds(u32x4 rsrc, uint32_t lds, int byte_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds), "v"(byte_off), "s"(rsrc) : "memory");
 }
 // transposing LDS read: see the kernel comment; returns this lane's 4 keys of one column
 __device__ __forceinline__ u32x2 lds_read_tr(const uint16_t *src) {
@@ -204,12 +216,10 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
     constexpr int LPW = CPR / 4;          // 1 KiB load instructions per wave, per tile, per tensor
     constexpr int NP = BF16 ? 2 : 1;      // P operands per product (hi, lo for bfloat16)
     constexpr int PF = 4;                 // LDS fragment requests kept ahead of the MFMAs
-    // four separate LDS objects: the compiler then knows that the loads flying into one buffer
-    // cannot alias the operand reads from the other and does not wait for them
-    __shared__ __attribute__((aligned(1024))) uint16_t K0[TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t K1[TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t V0[TILE];
-    __shared__ __attribute__((aligned(1024))) uint16_t V1[TILE];
+    // K[0], K[1], V[0], V[1]: tile t lives in K[t & 1], V[t & 1]
+    __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
+    const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)smem;  // LDS byte address
+    constexpr int TB = TILE * 2;                                        // bytes per tile
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -283,7 +293,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
     }
 
     // state of the item being started / computed
-    __amdgpu_buffer_rsrc_t rK, rV;
+    u32x4 rK, rV;
     // the item's entries, one per lane (at most 64, the planner cuts longer lists): requested
     // here, not touched before the item's first wait
     int raw_col = 0, raw_code0 = -2, raw_code1 = -2;
@@ -291,13 +301,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
     // Each wave has a private quarter of the second buffer pair (free between items): its 32 Q rows
     // are staged there (full-line requests instead of 32 partial lines per fragment load), and the
     // binary16 / bfloat16 output tile is transposed there into whole rows before it is stored.
-    uint16_t *const priv = (w < 2 ? K1 : V1) + (w & 1) * (32 * D);
+    uint16_t *const priv = smem + (w < 2 ? 1 : 3) * TILE + (w & 1) * (32 * D);
+    const uint32_t priv_lds = smem_base + ((w < 2 ? 1 : 3) * TILE + (w & 1) * (32 * D)) * 2;
     constexpr int NQL = CPR / 2;  // 1 KiB pieces of a 32-row slab
     // Request everything an item needs before its first tile can be computed.
     auto start_work = [&](const Work &wk) __attribute__((always_inline)) {
-        const __amdgpu_buffer_rsrc_t rQ = make_rsrc(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
-        rK = make_rsrc(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
-        rV = make_rsrc(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
+        const u32x4 rQ = make_rsrc4(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
+        rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
+        rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
         {
             const UEntry *u = p.uent + wk.begin + min(lane, max(wk.n - 1, 0));
             raw_col = __builtin_nontemporal_load(&u->col);
@@ -314,13 +325,13 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         for (int i = 0; i < NQL; ++i) {
             const int pchunk = i * 64 + lane_o;
             const int row = pchunk / CPR, pc = pchunk % CPR;
-            load_to_lds(rQ, priv + i * 512, (q0 + row) * (int)p.qs.s * 2 + (pc ^ swz_k<D>(row)) * 16);
+            load_to_lds(rQ, priv_lds + i * 1024, (q0 + row) * (int)p.qs.s * 2 + (pc ^ swz_k<D>(row)) * 16);
         }
         const int kb = wk.n > 0 ? wk.col0 * 64 * ksb : OOB, vb = wk.n > 0 ? wk.col0 * 64 * vsb : OOB;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            load_to_lds(rK, K0 + (w + 4 * i) * 512, k_go + (kb + i * RSTEP * ksb));
-            load_to_lds(rV, V0 + (w + 4 * i) * 512, v_go + (vb + i * RSTEP * vsb));
+            load_to_lds(rK, smem_base + (w + 4 * i) * 1024, k_go + (kb + i * RSTEP * ksb));
+            load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, v_go + (vb + i * RSTEP * vsb));
         }
     };
     // Invariant at the top of the loop: everything requested for the item has landed (each way
@@ -365,11 +376,11 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         ld_kb = t < n ? col * 64 * ksb : OOB;
         ld_vb = t < n ? col * 64 * vsb : OOB;
     };
-    auto load_piece = [&](int i, uint16_t *Kd, uint16_t *Vd) __attribute__((always_inline)) {  // i in [0, 2 LPW)
+    auto load_piece = [&](int i, uint32_t Kd, uint32_t Vd) __attribute__((always_inline)) {  // i in [0, 2 LPW); LDS byte addresses
         if (i & 1)
-            load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 512, v_go + (ld_vb + (i >> 1) * RSTEP * vsb));
+            load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 1024, v_go + (ld_vb + (i >> 1) * RSTEP * vsb));
         else
-            load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 512, k_go + (ld_kb + (i >> 1) * RSTEP * ksb));
+            load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, k_go + (ld_kb + (i >> 1) * RSTEP * ksb));
     };
 
     u32x4 qf[NS];  // Q^T operand: lane (j, hh) holds Q[q0 + j][16 s + 8 hh .. +8], read from the slab below
@@ -379,18 +390,16 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
     for (int dt = 0; dt < NDT; ++dt) o[dt] = zero16;
 
     // one tile for this wave
-    auto compute_tile = [&](const uint16_t *kp, const uint16_t *vp, uint16_t *Kn, uint16_t *Vn, int code, uint64_t word) __attribute__((always_inline)) {
-        if (code >= 0 && __builtin_amdgcn_ballot_w64(word != 0) == 0) {  // nothing for these 32 rows
-#pragma unroll
-            for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
-            return;
-        }
+    auto compute_tile = [&](int k_off, int v_off, uint32_t Kn, uint32_t Vn, int code, uint64_t word) __attribute__((always_inline)) {
+        // this tile's operand read addresses (bytes inside smem)
+        const int krd = k_rd + k_off, vrd = v_rd + v_off;
+        if (code >= 0 && __builtin_amdgcn_ballot_w64(word != 0) == 0) return;  // nothing for these 32 rows
         // scores, transposed: acc[kt][r] = S[q = j][key = 32 kt + 8 (r/4) + 4 hh + r%4].
         // Fragments are requested PF MFMAs ahead of their use (LDS latency is several MFMAs).
         f32x16 acc[2] = {zero16, zero16};
         auto k_addr = [&](int i) __attribute__((always_inline)) {  // i = 2 s + kt
             const int s = i >> 1, kt = i & 1;
-            return reinterpret_cast<const char *>(kp) + ((k_rd ^ (32 * s)) + 64 * kt * D);
+            return reinterpret_cast<const char *>(smem) + ((krd ^ (32 * s)) + 64 * kt * D);
         };
         u32x4 kfrag[PF];
 #pragma unroll
@@ -400,7 +409,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         for (int i = 0; i < 2 * NS; ++i) {  // the two accumulator chains alternate
             acc[i & 1] = mfma32<BF16>(kfrag[i % PF], qf[i >> 1], acc[i & 1]);
             if (i + PF < 2 * NS) kfrag[i % PF] = *reinterpret_cast<const u32x4 *>(k_addr(i + PF));
-            if ((i & 1) == 0) load_piece(i >> 1, Kn, Vn);  // next tile's loads ride under the MFMAs (2 NS = 4 LPW)
             __builtin_amdgcn_sched_barrier(0);
         }
         PHASE(2);
@@ -464,7 +472,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         // group cu+1 are issued between the MFMAs of group cu, so they run under the matrix pipe.
         auto v_frag = [&](int i) __attribute__((always_inline)) {  // i = cu * NDT + dt
             const int cu = i / NDT, dt = i % NDT;
-            const char *ptr = reinterpret_cast<const char *>(vp) + ((v_rd ^ (64 * dt)) + 32 * cu * D);
+            const char *ptr = reinterpret_cast<const char *>(smem) + ((vrd ^ (64 * dt)) + 32 * cu * D);
             const u32x2 lo = lds_read_tr(reinterpret_cast<const uint16_t *>(ptr)), hi = lds_read_tr(reinterpret_cast<const uint16_t *>(ptr + 16 * D));
             return u32x4{lo[0], lo[1], hi[0], hi[1]};
         };
@@ -516,17 +524,16 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
 #ifdef SMHA_DEV
     if (p.dbg & 256) tprev = __builtin_readcyclecounter();
 #endif
-    auto step = [&](int t, uint16_t *Kc, uint16_t *Vc, uint16_t *Kn, uint16_t *Vn) __attribute__((always_inline)) {
+    for (int t = 0; t < n; ++t) {
+        const int par = t & 1;
         const int code_next = entry_code(t + 1);
         const uint64_t word_next = fetch_word(code_next);
         load_begin(t + 1);
-        PHASE(0);
-        if (code != -2) {
-            compute_tile(Kc, Vc, Kn, Vn, code, word);
-        } else {
+        const uint32_t Kn = smem_base + (par ^ 1) * TB, Vn = smem_base + (2 + (par ^ 1)) * TB;
 #pragma unroll
-            for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
-        }
+        for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
+        PHASE(0);
+        if (code != -2) compute_tile(par * TB, (2 + par) * TB, Kn, Vn, code, word);
         PHASE(4);
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tile t+1 landed, own LDS reads done
         PHASE(6);
@@ -534,10 +541,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const Fwd
         PHASE(5);
         code = code_next;
         word = word_next;
-    };
-    for (int t = 0; t < n; t += 2) {
-        step(t, K0, V0, K1, V1);
-        if (t + 1 < n) step(t + 1, K1, V1, K0, V0);
     }
 
     STAMP(3);
