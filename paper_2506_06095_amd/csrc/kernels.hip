@@ -208,7 +208,7 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
 #endif
 
 template <int D, bool BF16, int OUT>
-__global__ void __launch_bounds__(256, D == 64 ? 3 : 2) smha_block_fwd(const FwdParams p) {
+__global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
     constexpr int TILE = 64 * D;          // one K or V tile, in elements
@@ -929,7 +929,7 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     fp.n_work = 8 * groups * plan->max_items;
     if (fp.n_work == 0) return hipSuccess;
     // two workgroups fit a CU (LDS at d = 128, registers at both head sizes)
-    unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 3 : 2) * plan->n_cu);
+    unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 4 : 2) * plan->n_cu);
 #ifdef SMHA_DEV
     if (const char *g = getenv("SMHA_GRID")) grid = (unsigned)atoi(g);
 #endif
