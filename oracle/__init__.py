@@ -41,6 +41,11 @@ def _load():
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                 ctypes.c_int, ctypes.c_int, ctypes.c_double, f64p]
         lib.oracle_masked_attention.restype = ctypes.c_int
+        lib.oracle_masked_attention_rect.argtypes = [u16p, u16p, u16p, ctypes.c_int, u8p, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                     ctypes.c_double, f64p]
+        lib.oracle_masked_attention_rect.restype = ctypes.c_int
         lib.oracle_row_probs.argtypes = [u16p, u16p, u16p, ctypes.c_int, u8p, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_double, ctypes.c_int, ctypes.c_int,
@@ -62,12 +67,13 @@ def _p(a, ct):
 def _check(Q, K, V, mask):
     for a in (Q, K, V):
         assert a.dtype == np.uint16 and a.ndim == 4 and a.flags.c_contiguous
-    assert Q.shape == K.shape == V.shape
+    assert K.shape == V.shape and Q.shape[:2] == K.shape[:2] and Q.shape[3] == K.shape[3]
     assert mask.dtype == np.uint8 and mask.ndim == 4 and mask.flags.c_contiguous
-    B, H, S, d = Q.shape
+    B, H, Sq, d = Q.shape
+    Sk = K.shape[2]
     Bm, Hm = mask.shape[:2]
-    assert mask.shape[2:] == (S, S)
-    return B, H, S, d, Bm, Hm
+    assert mask.shape[2:] == (Sq, Sk)
+    return B, H, Sq, Sk, d, Bm, Hm
 
 
 def num_threads() -> int:
@@ -75,24 +81,25 @@ def num_threads() -> int:
 
 
 def masked_attention(Q, K, V, dtype: str, mask, scale: float | None = None) -> np.ndarray:
-    """Q, K, V: uint16 bit patterns [B,H,S,d] ('f16' | 'bf16'); mask uint8
-    [Bm,Hm,S,S]; returns float64 [B,H,S,d]."""
-    B, H, S, d, Bm, Hm = _check(Q, K, V, mask)
+    """Q: uint16 bit patterns [B,H,Sq,d] ('f16' | 'bf16'); K, V: [B,H,Sk,d]; mask uint8
+    [Bm,Hm,Sq,Sk]; returns float64 [B,H,Sq,d].  Sq = Sk is self-attention."""
+    B, H, Sq, Sk, d, Bm, Hm = _check(Q, K, V, mask)
     if scale is None:
         scale = 1.0 / np.sqrt(float(d))
-    O = np.empty((B, H, S, d), dtype=np.float64)
-    rc = _load().oracle_masked_attention(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
-                                         _p(V, ctypes.c_uint16), 0 if dtype == "f16" else 1,
-                                         _p(mask, ctypes.c_uint8), Bm, Hm, B, H, S, d,
-                                         float(scale), _p(O, ctypes.c_double))
+    O = np.empty((B, H, Sq, d), dtype=np.float64)
+    rc = _load().oracle_masked_attention_rect(_p(Q, ctypes.c_uint16), _p(K, ctypes.c_uint16),
+                                              _p(V, ctypes.c_uint16), 0 if dtype == "f16" else 1,
+                                              _p(mask, ctypes.c_uint8), Bm, Hm, B, H, Sq, Sk, d,
+                                              float(scale), _p(O, ctypes.c_double))
     if rc != 0:
-        raise RuntimeError("oracle_masked_attention failed")
+        raise RuntimeError("oracle_masked_attention_rect failed")
     return O
 
 
 def row_probs(Q, K, V, dtype: str, mask, b: int, h: int, i: int, scale: float | None = None):
     """(probabilities[S], output[d]) of one query row, for invariant checks."""
-    B, H, S, d, Bm, Hm = _check(Q, K, V, mask)
+    B, H, S, Sk, d, Bm, Hm = _check(Q, K, V, mask)
+    assert S == Sk
     if scale is None:
         scale = 1.0 / np.sqrt(float(d))
     probs = np.empty(S, dtype=np.float64)

@@ -102,28 +102,31 @@ static void attend_row(const double *q, const double *K, const double *V, const 
 }
 
 /*
- * Q, K, V: [B][H][S][d] bit patterns (dtype 0 = binary16, 1 = bfloat16), packed.
- * mask:    [Bm][Hm][S][S] bytes, nonzero = attend; Bm in {1,B}, Hm in {1,H}.
- * O:       [B][H][S][d] doubles.
+ * The definition above does not need as many queries as keys (cross-attention, a decoding step
+ * against cached keys, or simply a sample of the query rows of a long sequence):
+ * Q:       [B][H][Sq][d] bit patterns (dtype 0 = binary16, 1 = bfloat16), packed.
+ * K, V:    [B][H][Sk][d].
+ * mask:    [Bm][Hm][Sq][Sk] bytes, nonzero = attend; Bm in {1,B}, Hm in {1,H}.
+ * O:       [B][H][Sq][d] doubles.
  * Returns 0, or -1 on bad arguments / allocation failure.
  */
-int oracle_masked_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int dtype,
-                            const uint8_t *mask, int Bm, int Hm,
-                            int B, int H, int S, int d, double scale, double *O)
+int oracle_masked_attention_rect(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int dtype,
+                                 const uint8_t *mask, int Bm, int Hm,
+                                 int B, int H, int Sq, int Sk, int d, double scale, double *O)
 {
-    if (!Q || !K || !V || !mask || !O || B < 1 || H < 1 || S < 1 || d < 1) return -1;
+    if (!Q || !K || !V || !mask || !O || B < 1 || H < 1 || Sq < 1 || Sk < 1 || d < 1) return -1;
     if ((Bm != 1 && Bm != B) || (Hm != 1 && Hm != H) || (dtype != 0 && dtype != 1)) return -1;
-    size_t n = (size_t)B * H * S * d;
-    double *q = malloc(n * sizeof *q), *k = malloc(n * sizeof *k), *v = malloc(n * sizeof *v);
+    size_t nq = (size_t)B * H * Sq * d, nk = (size_t)B * H * Sk * d;
+    double *q = malloc(nq * sizeof *q), *k = malloc(nk * sizeof *k), *v = malloc(nk * sizeof *v);
     if (!q || !k || !v) { free(q); free(k); free(v); return -1; }
-    widen(Q, q, n, dtype);
-    widen(K, k, n, dtype);
-    widen(V, v, n, dtype);
+    widen(Q, q, nq, dtype);
+    widen(K, k, nk, dtype);
+    widen(V, v, nk, dtype);
     int fail = 0;
-    long rows = (long)B * H * S;
+    long rows = (long)B * H * Sq;
 #pragma omp parallel
     {
-        double *s = malloc((size_t)S * sizeof *s);
+        double *s = malloc((size_t)Sk * sizeof *s);
         if (!s) {
 #pragma omp atomic write
             fail = 1;
@@ -131,19 +134,27 @@ int oracle_masked_attention(const uint16_t *Q, const uint16_t *K, const uint16_t
 #pragma omp for schedule(dynamic, 16)
         for (long r = 0; r < rows; ++r) {
             if (!s) continue;
-            int i = (int)(r % S);
-            int h = (int)((r / S) % H);
-            int b = (int)(r / ((long)S * H));
-            size_t bh = ((size_t)b * H + h) * S * d;
+            int i = (int)(r % Sq);
+            int h = (int)((r / Sq) % H);
+            int b = (int)(r / ((long)Sq * H));
+            size_t bhq = ((size_t)b * H + h) * Sq * d, bhk = ((size_t)b * H + h) * Sk * d;
             const uint8_t *mrow = mask +
-                ((((size_t)(Bm == 1 ? 0 : b)) * Hm + (Hm == 1 ? 0 : h)) * S + i) * (size_t)S;
-            attend_row(q + bh + (size_t)i * d, k + bh, v + bh, mrow, S, d, scale, s,
-                       O + bh + (size_t)i * d, NULL);
+                ((((size_t)(Bm == 1 ? 0 : b)) * Hm + (Hm == 1 ? 0 : h)) * Sq + i) * (size_t)Sk;
+            attend_row(q + bhq + (size_t)i * d, k + bhk, v + bhk, mrow, Sk, d, scale, s,
+                       O + bhq + (size_t)i * d, NULL);
         }
         free(s);
     }
     free(q); free(k); free(v);
     return fail ? -1 : 0;
+}
+
+/* Self-attention: as many queries as keys, mask [Bm][Hm][S][S]. */
+int oracle_masked_attention(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int dtype,
+                            const uint8_t *mask, int Bm, int Hm,
+                            int B, int H, int S, int d, double scale, double *O)
+{
+    return oracle_masked_attention_rect(Q, K, V, dtype, mask, Bm, Hm, B, H, S, S, d, scale, O);
 }
 
 /* Probabilities of a single query row (b, h, i): probs[S].  For invariant tests. */

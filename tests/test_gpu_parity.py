@@ -116,6 +116,49 @@ def test_config_5_full_size_sampled_heads(torch_mod, smha):
     assert np.all(np.abs(got[:, :, :valid, :]).sum(axis=-1) > 0)
 
 
+LONG = {
+    # BigBird blocks with padding, as cfg5, at twice and eight times its length
+    "bigbird_16k": (16384, 128, "f16", lambda S: W.MaskSpec(flags=W.BIGBIRD | W.PADDING, block=64, n_window_blocks=3,
+                                                           n_global_blocks=2, n_random_blocks=3, seed=16,
+                                                           per_head=True, valid_len=(S - 777,))),
+    "bigbird_64k": (65536, 64, "bf16", lambda S: W.MaskSpec(flags=W.BIGBIRD, block=64, n_window_blocks=3,
+                                                           n_global_blocks=1, n_random_blocks=2, seed=64)),
+    # causal band plus strided columns (cfg3's pattern) and a Longformer band with global tokens
+    "strided_causal_16k": (16384, 64, "f16", lambda S: W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=255,
+                                                                 stride=256, stride_phase=3)),
+    "longformer_64k": (65536, 128, "f16", lambda S: W.MaskSpec(flags=W.WINDOW | W.GLOBAL, window_left=128,
+                                                              window_right=128, n_global=16)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(LONG))
+def test_long_sequences_on_sampled_rows(torch_mod, smha, name):
+    """Sequences of 16k and 64k (the paper reports up to 64k, Sec. 5.5): the whole output is computed on the
+    GPU; the oracle recomputes a sample of query rows (first / last rows, tile edges, random ones) from mask
+    rows generated on their own, never the S x S matrix."""
+    S, d, dtype, make = LONG[name]
+    spec = make(S)
+    B, H = 1, 2
+    Q, K, V = W.qkv_bits(B, H, S, d, dtype, 0.7, seed=S + d)
+    rng = np.random.default_rng(S)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 63, 64, 127, 128, S // 2 - 1, S // 2, S - 778, S - 777, S - 65, S - 64, S - 1],
+                                     rng.integers(0, S, 24)]))
+    with smha.Plan.from_desc(spec, B, H, S, block=64, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        q, k, v = (to_dev(torch_mod, x, dtype) for x in (Q, K, V))
+        out = plan.forward(q, k, v, out_dtype=torch_mod.float32)
+        torch_mod.cuda.synchronize()
+        got = out[:, :, torch_mod.from_numpy(rows).cuda()].cpu().numpy()
+        whole_finite = bool(torch_mod.isfinite(out).all())
+    assert whole_finite
+    valid = int(spec.valid_len[0]) if spec.valid_len else S
+    Hm = spec.n_head_masks(H)
+    mrows = np.stack([W.mask_rows(spec, S, h, valid, rows) for h in range(Hm)])[None].astype(np.uint8)
+    ref = oracle.masked_attention(np.ascontiguousarray(Q[:, :, rows]), K, V, dtype, np.ascontiguousarray(mrows))
+    check(got, ref, name)
+    if spec.valid_len:
+        assert np.all(got[:, :, rows >= valid] == 0.0)
+
+
 @pytest.mark.parametrize("kernel", ["block", "row"])
 @pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
 def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):

@@ -134,11 +134,11 @@ def test_causal_first_row_and_zero_width_window():
 
 def brute_force(q, k, v, m, scale):
     """Dense scores with -inf fill, then a whole-row softmax: pure Python."""
-    S, d = len(q), len(q[0])
-    out = [[0.0] * d for _ in range(S)]
-    for i in range(S):
+    d = len(q[0])
+    out = [[0.0] * d for _ in range(len(q))]
+    for i in range(len(q)):
         row = []
-        for j in range(S):
+        for j in range(len(k)):
             if m[i][j]:
                 row.append(scale * math.fsum(q[i][t] * k[j][t] for t in range(d)))
             else:
@@ -149,7 +149,7 @@ def brute_force(q, k, v, m, scale):
         e = [math.exp(x - top) for x in row]
         z = math.fsum(e)
         for t in range(d):
-            out[i][t] = math.fsum(e[j] / z * v[j][t] for j in range(S))
+            out[i][t] = math.fsum(e[j] / z * v[j][t] for j in range(len(k)))
     return out
 
 
@@ -164,6 +164,61 @@ def test_brute_force_on_tiny_shapes(S, d, seed):
     q, k, v = (W.bits_to_f64(x, "f16")[0, 0].tolist() for x in (Q, K, V))
     ref = np.array(brute_force(q, k, v, mask[0, 0].tolist(), 0.37))
     assert np.abs(got[0, 0] - ref).max() < 1e-14
+
+
+# -- fewer (or more) queries than keys ---------------------------------------
+
+def rand_rect(B, H, Sq, Sk, d, dtype="f16", seed=0, std=1.0):
+    Q, _, _ = W.qkv_bits(B, H, Sq, d, dtype, std, seed)
+    _, K, V = W.qkv_bits(B, H, Sk, d, dtype, std, seed + 1)
+    return Q, K, V
+
+
+@pytest.mark.parametrize("Sq,Sk", [(1, 9), (5, 3), (7, 16)])
+def test_rectangular_all_ones_equals_dense_attention_and_brute_force(Sq, Sk):
+    Q, K, V = rand_rect(2, 2, Sq, Sk, 8, seed=40 + Sq)
+    ones = np.ones((1, 1, Sq, Sk), dtype=np.uint8)
+    got = oracle.masked_attention(Q, K, V, "f16", ones)
+    assert got.shape == (2, 2, Sq, 8)
+    assert np.abs(got - dense_softmax_attention(Q, K, V, "f16")).max() < 1e-12
+    rng = np.random.default_rng(Sq * 31 + Sk)
+    mask = (rng.random((2, 2, Sq, Sk)) < 0.5).astype(np.uint8)
+    mask[1, 0, 0, :] = 0  # one fully masked row
+    got = oracle.masked_attention(Q, K, V, "f16", mask, scale=0.41)
+    for b in range(2):
+        for h in range(2):
+            q, k, v = (W.bits_to_f64(x, "f16")[b, h].tolist() for x in (Q, K, V))
+            ref = np.array(brute_force(q, k, v, mask[b, h].tolist(), 0.41))
+            assert np.abs(got[b, h] - ref).max() < 1e-14
+    assert np.all(got[1, 0, 0] == 0.0)
+
+
+def test_rectangular_closed_forms_and_row_subsets():
+    # one key per query -> exactly that value row; zero queries -> mean over the unmasked keys
+    Sq, Sk, d = 6, 11, 5
+    Q, K, V = rand_rect(1, 2, Sq, Sk, d, seed=77)
+    v = W.bits_to_f64(V, "f16")
+    pick = np.array([10, 0, 3, 3, 7, 1])
+    mask = np.zeros((1, 1, Sq, Sk), dtype=np.uint8)
+    mask[0, 0, np.arange(Sq), pick] = 1
+    got = oracle.masked_attention(Q, K, V, "f16", mask)
+    assert np.array_equal(got[0, 1], v[0, 1, pick])
+    rng = np.random.default_rng(5)
+    mask = (rng.random((1, 1, Sq, Sk)) < 0.6).astype(np.uint8)
+    mask[0, 0, :, 2] = 1
+    got = oracle.masked_attention(np.zeros_like(Q), K, V, "f16", mask)
+    for i in range(Sq):
+        sel = mask[0, 0, i].astype(bool)
+        assert np.abs(got[0, 0, i] - v[0, 0, sel].mean(axis=0)).max() < 1e-14
+    # a sample of the query rows of a self-attention problem gives those rows of its result, bit for bit
+    S = 33
+    Q, K, V = rand_qkv(1, 2, S, 8, seed=78)
+    full_mask = W.dense_mask(W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=4, stride=8), 1, 2, S)
+    full = oracle.masked_attention(Q, K, V, "f16", full_mask)
+    rows = np.array([0, 5, 17, 32])
+    part = oracle.masked_attention(np.ascontiguousarray(Q[:, :, rows]), K, V, "f16",
+                                   np.ascontiguousarray(full_mask[:, :, rows]))
+    assert np.array_equal(part, full[:, :, rows])
 
 
 def test_default_scale_is_inverse_sqrt_head_dim():

@@ -83,15 +83,18 @@ class MaskSpec:
         return H if (self.per_head and has_random) else 1
 
 
-def _one_mask(spec: MaskSpec, S: int, head: int, valid: int) -> np.ndarray:
-    i = np.arange(S)[:, None]
+def mask_rows(spec: MaskSpec, S: int, head: int, valid: int, rows) -> np.ndarray:
+    """bool [len(rows), S]: the given query rows of the S x S mask (the composition rule above,
+    evaluated only where asked: long sequences never need the whole matrix)."""
+    rows = np.asarray(rows, dtype=np.int64)
+    i = rows[:, None]
     j = np.arange(S)[None, :]
     f = spec.flags
     additive = f & (WINDOW | GLOBAL | STRIDED | BLOCK_RANDOM | BIGBIRD)
     if not additive:
-        m = np.ones((S, S), dtype=bool)
+        m = np.ones((len(rows), S), dtype=bool)
     else:
-        m = np.zeros((S, S), dtype=bool)
+        m = np.zeros((len(rows), S), dtype=bool)
     if f & WINDOW:
         m |= ((i - j) <= spec.window_left) & ((j - i) <= spec.window_right)
     if f & GLOBAL:
@@ -101,32 +104,38 @@ def _one_mask(spec: MaskSpec, S: int, head: int, valid: int) -> np.ndarray:
     if f & (BLOCK_RANDOM | BIGBIRD):
         bs = spec.block
         nb = -(-S // bs)
-        keep = np.zeros((nb, nb), dtype=bool)
-        if f & BLOCK_RANDOM:
-            for br in range(nb):
+        keep = {}
+        for br in sorted(set(int(r) // bs for r in rows)):
+            row = np.zeros(nb, dtype=bool)
+            if f & BLOCK_RANDOM:
                 for bc in range(nb):
                     if br == bc or hash_to_unit(block_hash(spec.seed, head, br, bc)) < spec.keep_p:
-                        keep[br, bc] = True
-        if f & BIGBIRD:
-            half = (spec.n_window_blocks - 1) // 2
-            for br in range(nb):
-                row = np.zeros(nb, dtype=bool)
+                        row[bc] = True
+            if f & BIGBIRD:
+                big = np.zeros(nb, dtype=bool)
+                half = (spec.n_window_blocks - 1) // 2
                 if spec.n_window_blocks > 0:
-                    row[max(0, br - half):min(nb, br + half + 1)] = True
-                row[:min(nb, spec.n_global_blocks)] = True
+                    big[max(0, br - half):min(nb, br + half + 1)] = True
+                big[:min(nb, spec.n_global_blocks)] = True
                 if br < spec.n_global_blocks:
-                    row[:] = True
-                cand = [bc for bc in range(nb) if not row[bc]]
+                    big[:] = True
+                cand = [bc for bc in range(nb) if not big[bc]]
                 cand.sort(key=lambda bc: (block_hash(spec.seed, head, br, bc), bc))
                 for bc in cand[:spec.n_random_blocks]:
-                    row[bc] = True
-                keep[br] |= row
-        m |= np.repeat(np.repeat(keep, bs, axis=0), bs, axis=1)[:S, :S]
+                    big[bc] = True
+                row |= big
+            keep[br] = np.repeat(row, bs)[:S]
+        for t, r in enumerate(rows):
+            m[t] |= keep[int(r) // bs]
     if f & CAUSAL:
         m &= j <= i
     if f & PADDING:
         m &= (i < valid) & (j < valid)
     return m
+
+
+def _one_mask(spec: MaskSpec, S: int, head: int, valid: int) -> np.ndarray:
+    return mask_rows(spec, S, head, valid, np.arange(S))
 
 
 def dense_mask(spec: MaskSpec, B: int, H: int, S: int) -> np.ndarray:
