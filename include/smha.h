@@ -13,7 +13,9 @@
  * Conventions
  *   - A mask entry of 1 means "query i attends key j".  A query with no unmasked key
  *     produces an all-zero output row (the paper does not define this case).
- *   - Sq = Sk = S.  head_dim d is 64 or 128.  Q/K/V are IEEE binary16 or bfloat16.
+ *   - Self-attention has Sq = Sk = S; a dense mask may also have fewer or more queries than
+ *     keys (smha_plan_from_dense_rect: cross-attention, a chunk of queries against cached
+ *     keys).  head_dim d is 64 or 128.  Q/K/V are IEEE binary16 or bfloat16.
  *   - All functions return a status code; nothing is printed, thrown or aborted.
  *     On error, output parameters are left untouched.
  *   - "host" / "device" is stated per pointer.  The library never frees or keeps
@@ -93,7 +95,7 @@ typedef struct {
 } smha_mask_desc_t;
 
 typedef struct {
-    int S, Bm, Hm;      /* sequence length; masks are [Bm][Hm][S][S], Bm in {1,B}, Hm in {1,H} */
+    int S, Bm, Hm;      /* queries per sequence; masks are [Bm][Hm][S][Sk], Bm in {1,B}, Hm in {1,H} */
     int block;          /* tile edge of the exported block format                               */
     int kernel;         /* SMHA_KERNEL_ROW or SMHA_KERNEL_BLOCK: what smha_forward will run     */
     int has_row_format, has_block_kernel_lists, on_device;
@@ -106,6 +108,7 @@ typedef struct {
     int64_t n_items, n_split_rows; /* block-kernel work items / 128-row groups split along keys  */
     double eq1_threshold; /* Eq. 1 with valid16 averaged over masks; < 0 means row-wise          */
     double model_row_us, model_block_us; /* calibrated cost model, per (batch, head) pair         */
+    int Sk;             /* keys per sequence (= S unless the plan came from smha_plan_from_dense_rect) */
 } smha_plan_info_t;
 
 /* Arrays smha_plan_export can copy out (all host byte order, packed):
@@ -144,6 +147,14 @@ typedef enum {
 smha_status_t smha_plan_from_dense(const uint8_t *mask, int mask_on_device, int Bm, int Hm, int S,
                                    const smha_plan_opts_t *opts, smha_plan_t **out);
 
+/* The same for a mask with Sq queries and Sk keys per sequence, uint8 [Bm][Hm][Sq][Sk] (the
+ * per-row definition of attention does not need Sq = Sk; Sec. 2.1.1).  Row arrays then have Sq + 1
+ * entries, tile rows cover queries and tile columns keys; for Eq. 1 the valid-tile ratio is taken
+ * over the ceil(Sq/16) * ceil(Sk/16) tiles and n = ceil(Sk/16).  smha_forward takes Q and O with
+ * Sq rows and K and V with Sk rows.  smha_plan_from_dense is the case Sq = Sk. */
+smha_status_t smha_plan_from_dense_rect(const uint8_t *mask, int mask_on_device, int Bm, int Hm, int Sq, int Sk,
+                                        const smha_plan_opts_t *opts, smha_plan_t **out);
+
 /* Mask analysis from a pattern description; B and H fix how many distinct masks exist
  * (Bm = B with PADDING else 1; Hm = H with per_head and a random component, else 1). */
 smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B, int H, int S,
@@ -161,7 +172,8 @@ smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_exp
 /* Fused masked attention (Sec. 4.2.2, Algorithm 1 for the block kernel; Sec. 4.1 for the
  * row-wise kernel).  Enqueues on `hip_stream` (a hipStream_t, NULL = default stream) and
  * returns without synchronising.
- *   Q, K, V         device, [B][H][S][d] of in_dtype, addressed through *_strides
+ *   Q               device, [B][H][S][d] of in_dtype, addressed through *_strides
+ *   K, V            device, [B][H][Sk][d] of in_dtype (Sk = S for self-attention plans)
  *   O               device, [B][H][S][d] of out_dtype (same as in_dtype, or SMHA_F32)
  *   *_strides       host, {batch, head, seq} strides in elements, d is contiguous;
  *                   NULL = packed.  Pointers must be 16-byte aligned, strides multiples of

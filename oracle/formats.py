@@ -40,18 +40,18 @@ def bsr(M: np.ndarray, bs: int):
     """Dictionary with load/full/part row_ptr + col_idx (int32), flags (uint8 per
     load entry: 1 = full, 0 = part) and bitmap (uint64 [npart][bs])."""
     assert bs in (16, 32, 64)
-    S = M.shape[0]
-    nb = -(-S // bs)
-    P = np.zeros((nb * bs, nb * bs), dtype=np.uint8)
-    P[:S, :S] = (M != 0)
-    cnt = P.reshape(nb, bs, nb, bs).sum(axis=(1, 3))
+    Sq, Sk = M.shape                      # tile rows cover queries, tile columns keys
+    nb, nbc = -(-Sq // bs), -(-Sk // bs)
+    P = np.zeros((nb * bs, nbc * bs), dtype=np.uint8)
+    P[:Sq, :Sk] = (M != 0)
+    cnt = P.reshape(nb, bs, nbc, bs).sum(axis=(1, 3))
     load_row_ptr = np.zeros(nb + 1, np.int32)
     full_row_ptr = np.zeros(nb + 1, np.int32)
     part_row_ptr = np.zeros(nb + 1, np.int32)
     load_col, full_col, part_col, flags, bitmaps = [], [], [], [], []
     weights = (np.uint64(1) << np.arange(bs, dtype=np.uint64))
     for br in range(nb):
-        for bc in range(nb):
+        for bc in range(nbc):
             c = int(cnt[br, bc])
             if c == 0:
                 continue
@@ -95,16 +95,17 @@ def bitmap_inner_tiles(bitmap_rows: np.ndarray) -> np.ndarray:
     return out
 
 
-def dense_from_csr(row_ptr, col_idx, S: int) -> np.ndarray:
-    M = np.zeros((S, S), dtype=np.uint8)
+def dense_from_csr(row_ptr, col_idx, S: int, Sk: int | None = None) -> np.ndarray:
+    M = np.zeros((S, S if Sk is None else Sk), dtype=np.uint8)
     for i in range(S):
         M[i, col_idx[row_ptr[i]:row_ptr[i + 1]]] = 1
     return M
 
 
-def dense_from_bsr(f: dict, S: int, bs: int) -> np.ndarray:
+def dense_from_bsr(f: dict, S: int, bs: int, Sk: int | None = None) -> np.ndarray:
+    Sk = S if Sk is None else Sk
     nb = -(-S // bs)
-    P = np.zeros((nb * bs, nb * bs), dtype=np.uint8)
+    P = np.zeros((nb * bs, -(-Sk // bs) * bs), dtype=np.uint8)
     part = 0
     for br in range(nb):
         for e in range(f["load_row_ptr"][br], f["load_row_ptr"][br + 1]):
@@ -118,4 +119,4 @@ def dense_from_bsr(f: dict, S: int, bs: int) -> np.ndarray:
                     w = int(words[r])
                     for c in range(bs):
                         P[br * bs + r, bc * bs + c] = (w >> c) & 1
-    return P[:S, :S]
+    return P[:S, :Sk]

@@ -54,7 +54,7 @@ class PlanInfo(C.Structure):
                 ("n_part", C.c_int64), ("n_valid16", C.c_int64), ("n_tiles64", C.c_int64), ("n_union", C.c_int64),
                 ("n_items", C.c_int64), ("n_split_rows", C.c_int64),
                 ("eq1_threshold", C.c_double), ("model_row_us", C.c_double),
-                ("model_block_us", C.c_double)]
+                ("model_block_us", C.c_double), ("Sk", C.c_int)]
 
 
 _lib = None
@@ -75,6 +75,9 @@ def _load():
     lib.smha_plan_from_dense.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int,
                                          C.POINTER(PlanOpts), C.POINTER(vp)]
     lib.smha_plan_from_dense.restype = C.c_int
+    lib.smha_plan_from_dense_rect.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                              C.POINTER(PlanOpts), C.POINTER(vp)]
+    lib.smha_plan_from_dense_rect.restype = C.c_int
     lib.smha_plan_from_desc.argtypes = [C.POINTER(MaskDesc), C.c_int, C.c_int, C.c_int,
                                         C.POINTER(PlanOpts), C.POINTER(vp)]
     lib.smha_plan_from_desc.restype = C.c_int
@@ -109,23 +112,39 @@ def _opts(block=0, force=SMHA_KERNEL_AUTO, selector=SMHA_SELECTOR_CALIBRATED, bu
 def smha_plan_from_dense(mask, **opts) -> int:
     """mask: numpy uint8 [Bm,Hm,S,S] (host) or a torch uint8/bool CUDA tensor (device).
     Returns the plan handle (an integer address)."""
+    if mask.ndim != 4 or mask.shape[2] != mask.shape[3]:
+        raise ValueError("mask must be [Bm,Hm,S,S]")
+    return _plan_from_dense(mask, False, **opts)
+
+
+def smha_plan_from_dense_rect(mask, **opts) -> int:
+    """mask: [Bm,Hm,Sq,Sk], numpy uint8 (host) or a 1-byte torch CUDA tensor (device)."""
+    if mask.ndim != 4:
+        raise ValueError("mask must be [Bm,Hm,Sq,Sk]")
+    return _plan_from_dense(mask, True, **opts)
+
+
+def _plan_from_dense(mask, rect: bool, **opts) -> int:
     lib = _load()
     if isinstance(mask, np.ndarray):
-        if mask.dtype != np.uint8 or mask.ndim != 4 or mask.shape[2] != mask.shape[3]:
-            raise ValueError("mask must be uint8 [Bm,Hm,S,S]")
+        if mask.dtype != np.uint8:
+            raise ValueError("mask must be uint8")
         m = np.ascontiguousarray(mask)
         ptr, on_dev = m.ctypes.data, 0
     else:  # torch tensor on the GPU
-        if mask.ndim != 4 or mask.shape[2] != mask.shape[3] or mask.element_size() != 1:
-            raise ValueError("mask must be a 1-byte [Bm,Hm,S,S] tensor")
+        if mask.element_size() != 1:
+            raise ValueError("mask must be a 1-byte tensor")
         m = mask.contiguous()
         ptr, on_dev = m.data_ptr(), (1 if m.is_cuda else 0)
-    Bm, Hm, S, _ = m.shape
+    Bm, Hm, Sq, Sk = m.shape
     out = C.c_void_p()
     o = _opts(**opts)
-    st = lib.smha_plan_from_dense(C.c_void_p(ptr), on_dev, Bm, Hm, S, C.byref(o), C.byref(out))
+    if rect:
+        st = lib.smha_plan_from_dense_rect(C.c_void_p(ptr), on_dev, Bm, Hm, Sq, Sk, C.byref(o), C.byref(out))
+    else:
+        st = lib.smha_plan_from_dense(C.c_void_p(ptr), on_dev, Bm, Hm, Sq, C.byref(o), C.byref(out))
     if st != 0:
-        raise SmhaError(st, "smha_plan_from_dense")
+        raise SmhaError(st, "smha_plan_from_dense_rect" if rect else "smha_plan_from_dense")
     return out.value
 
 
@@ -191,12 +210,19 @@ def _strides3(t):
 
 def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
                  stream=None) -> None:
-    """Q, K, V, O: torch CUDA tensors [B,H,S,d]; O in the input dtype or float32.
-    Enqueues on `stream` (default: torch's current stream); does not synchronise."""
+    """Q, O: torch CUDA tensors [B,H,S,d]; K, V: [B,H,Sk,d] (S and Sk as in the plan); O in the
+    input dtype or float32.  Enqueues on `stream` (default: torch's current stream); does not
+    synchronise."""
     import torch
     B, H, S, d = Q.shape
-    if K.shape != Q.shape or V.shape != Q.shape or O.shape != Q.shape:
-        raise ValueError("Q, K, V, O must share one [B,H,S,d] shape")
+    info = PlanInfo()
+    st = _load().smha_plan_info(C.c_void_p(plan), C.byref(info))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_info")
+    if O.shape != Q.shape or K.shape != V.shape or K.shape[:2] != Q.shape[:2] or K.shape[3] != d:
+        raise ValueError("Q, O must be [B,H,S,d] and K, V [B,H,Sk,d]")
+    if S != info.S or K.shape[2] != info.Sk:
+        raise ValueError(f"the plan is for {info.S} queries and {info.Sk} keys per sequence")
     codes = {torch.float16: SMHA_F16, torch.bfloat16: SMHA_BF16, torch.float32: SMHA_F32}
     if Q.dtype not in (torch.float16, torch.bfloat16) or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise ValueError("Q, K, V must be float16 or bfloat16")
@@ -223,6 +249,10 @@ class Plan:
     @classmethod
     def from_dense(cls, mask, **opts) -> "Plan":
         return cls(smha_plan_from_dense(mask, **opts))
+
+    @classmethod
+    def from_dense_rect(cls, mask, **opts) -> "Plan":
+        return cls(smha_plan_from_dense_rect(mask, **opts))
 
     @classmethod
     def from_desc(cls, spec, B: int, H: int, S: int, **opts) -> "Plan":

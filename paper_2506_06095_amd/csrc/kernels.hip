@@ -35,7 +35,7 @@ struct FwdParams {
     const uint16_t *Q, *K, *V;
     void *O;
     Strides qs, ks, vs, os;
-    int B, H, S, Bm, Hm;
+    int B, H, S, Sk, Bm, Hm;  // S queries, Sk keys
     int out_dtype;  // smha_dtype_t
     float c;        // scale * log2(e)
     // block path
@@ -307,8 +307,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // Request everything an item needs before its first tile can be computed.
     auto start_work = [&](const Work &wk) __attribute__((always_inline)) {
         const u32x4 rQ = make_rsrc4(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
-        rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(S - 1) * p.ks.s + D) * 2);
-        rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(S - 1) * p.vs.s + D) * 2);
+        rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(p.Sk - 1) * p.ks.s + D) * 2);
+        rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(p.Sk - 1) * p.vs.s + D) * 2);
         {
             const UEntry *u = p.uent + wk.begin + min(lane, max(wk.n - 1, 0));
             raw_col = __builtin_nontemporal_load(&u->col);
@@ -796,12 +796,13 @@ int current_device_or_negative() {
 // Mask intake on the device (Sec. 4.2.1: the mask is analysed once): a dense byte mask is
 // packed into bit rows, one thread per 64-bit word = 64 mask bytes, so that only S*S/8 bytes
 // cross to the host for the format analysis.  HBM-bound: S*S bytes read, S*S/8 written per mask.
-// words[(mask*S + i) * W + t] bit c = (mask[i][64 t + c] != 0), entries past S are 0.
+// Rows have S entries (the key side); words[row * W + t] bit c = (row[64 t + c] != 0), entries
+// past S are 0, where row runs over all query rows of all masks.
 __global__ void __launch_bounds__(256) smha_mask_pack_bits(const uint8_t *__restrict__ mask, uint64_t *__restrict__ words,
                                                            int S, int W, long long n_words) {
     const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= n_words) return;
-    const long long row = g / W;  // mask * S + i
+    const long long row = g / W;
     const int t = (int)(g - row * W);
     const uint8_t *src = mask + row * S + 64 * (long long)t;
     const int n = min(64, S - 64 * t);
@@ -827,16 +828,16 @@ __global__ void __launch_bounds__(256) smha_mask_pack_bits(const uint8_t *__rest
     words[g] = out;
 }
 
-smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int S, uint64_t *host_words) {
-    const int W = (S + 63) / 64;
-    const long long n_words = (long long)n_masks * S * W;
+smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int Sk, uint64_t *host_words) {
+    const int W = (Sk + 63) / 64;
+    const long long n_words = (long long)n_masks * Sq * W;
     uint64_t *d_words = nullptr;
     if (hipMalloc(reinterpret_cast<void **>(&d_words), (size_t)n_words * 8) != hipSuccess) {
         (void)hipGetLastError();
         return SMHA_ERR_ALLOC;
     }
     const unsigned grid = (unsigned)((n_words + 255) / 256);
-    hipLaunchKernelGGL(smha_mask_pack_bits, dim3(grid), dim3(256), 0, 0, dev_mask, d_words, S, W, n_words);
+    hipLaunchKernelGGL(smha_mask_pack_bits, dim3(grid), dim3(256), 0, 0, dev_mask, d_words, Sk, W, n_words);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipMemcpy(host_words, d_words, (size_t)n_words * 8, hipMemcpyDeviceToHost);
     (void)hipFree(d_words);
@@ -979,11 +980,11 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     if ((int64_t)B * H > (1 << 24)) return SMHA_ERR_UNSUPPORTED;
     {   // the block kernel addresses one head's Q/K/V/O through 32-bit buffer offsets
         const int64_t lim = (int64_t)1 << 31;
-        const int64_t rows = (int64_t)plan->S + 128;
+        const int64_t rows = (int64_t)plan->S + 128, krows = (int64_t)plan->Sk + 128;
         const int64_t qs = q_strides ? q_strides[2] : d, ks = k_strides ? k_strides[2] : d, vs = v_strides ? v_strides[2] : d;
         const int64_t os = o_strides ? o_strides[2] : d;
         if (qs < d || ks < d || vs < d || os < d) return SMHA_ERR_UNSUPPORTED;  // rows must not overlap
-        if ((rows * qs + d) * 2 >= lim || (rows * ks + d) * 2 >= lim || (rows * vs + d) * 2 >= lim ||
+        if ((rows * qs + d) * 2 >= lim || (krows * ks + d) * 2 >= lim || (krows * vs + d) * 2 >= lim ||
             (rows * os + d) * 2 >= lim)
             return SMHA_ERR_UNSUPPORTED;
     }
@@ -997,15 +998,14 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
         return SMHA_ERR_HIP;
     }
 
-    const int S = plan->S;
-    auto packed = [&](Strides &s) { s.s = d; s.h = (int64_t)S * d; s.b = (int64_t)H * S * d; };
-    auto take = [&](Strides &s, const int64_t *in) {
-        if (in) { s.b = in[0]; s.h = in[1]; s.s = in[2]; } else packed(s);
+    const int S = plan->S, Sk = plan->Sk;
+    auto take = [&](Strides &s, const int64_t *in, int rows) {
+        if (in) { s.b = in[0]; s.h = in[1]; s.s = in[2]; } else { s.s = d; s.h = (int64_t)rows * d; s.b = (int64_t)H * rows * d; }
     };
     FwdParams fp{};
     fp.Q = (const uint16_t *)Q; fp.K = (const uint16_t *)K; fp.V = (const uint16_t *)V; fp.O = O;
-    take(fp.qs, q_strides); take(fp.ks, k_strides); take(fp.vs, v_strides); take(fp.os, o_strides);
-    fp.B = B; fp.H = H; fp.S = S; fp.Bm = plan->Bm; fp.Hm = plan->Hm;
+    take(fp.qs, q_strides, S); take(fp.ks, k_strides, Sk); take(fp.vs, v_strides, Sk); take(fp.os, o_strides, S);
+    fp.B = B; fp.H = H; fp.S = S; fp.Sk = Sk; fp.Bm = plan->Bm; fp.Hm = plan->Hm;
     fp.out_dtype = out_dtype;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;

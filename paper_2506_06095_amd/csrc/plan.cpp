@@ -19,7 +19,7 @@ namespace {
 // ---------------------------------------------------------------------------------------
 struct RowSource {
     virtual ~RowSource() = default;
-    virtual void row_bits(int i, uint64_t *words) const = 0;  // words[W], W = ceil(S/64)
+    virtual void row_bits(int i, uint64_t *words) const = 0;  // words[W], W = ceil(Sk/64)
 };
 
 inline void set_range(uint64_t *w, int lo, int hi) {  // bits [lo, hi)
@@ -181,13 +181,13 @@ inline uint64_t extract_bits(const uint64_t *row, int c0, int n) {  // n <= 64, 
     return n == 64 ? w : (w & ((1ull << n) - 1));
 }
 
-void analyse_stripe(const RowSource &src, int S, int block, bool want_rows, int stripe,
+void analyse_stripe(const RowSource &src, int Sq, int Sk, int block, bool want_rows, int stripe,
                     uint64_t *bits /* 64*W */, Stripe &out) {
-    const int W = (S + 63) / 64;
+    const int W = (Sk + 63) / 64;
     const int r0 = stripe * 64;
     for (int r = 0; r < 64; ++r) {
         uint64_t *w = bits + (size_t)r * W;
-        if (r0 + r < S)
+        if (r0 + r < Sq)
             src.row_bits(r0 + r, w);
         else
             std::memset(w, 0, sizeof(uint64_t) * W);
@@ -211,7 +211,7 @@ void analyse_stripe(const RowSource &src, int S, int block, bool want_rows, int 
     }
     // non-empty 16x16 tiles (input of the paper's Eq. 1)
     for (int g = 0; g < 4; ++g) {
-        if (r0 + g * 16 >= S) break;
+        if (r0 + g * 16 >= Sq) break;
         for (int t = 0; t < W; ++t) {
             uint64_t any = 0;
             for (int r = 0; r < 16; ++r) any |= bits[(size_t)(g * 16 + r) * W + t];
@@ -220,10 +220,10 @@ void analyse_stripe(const RowSource &src, int S, int block, bool want_rows, int 
         }
     }
     // tiles of edge `block`
-    const int nb = (S + block - 1) / block;
+    const int nb = (Sk + block - 1) / block;
     const int per = 64 / block;
     for (int sub = 0; sub < per; ++sub) {
-        if (r0 + sub * block >= S) break;
+        if (r0 + sub * block >= Sq) break;
         for (int bc = 0; bc < nb; ++bc) {
             uint64_t words[64];
             int cnt = 0;
@@ -258,23 +258,23 @@ void analyse_stripe(const RowSource &src, int S, int block, bool want_rows, int 
     }
 }
 
-smha_status_t analyse_mask(const RowSource &src, int S, int block, bool want_rows,
+smha_status_t analyse_mask(const RowSource &src, int Sq, int Sk, int block, bool want_rows,
                            MaskFormats &mf) {
-    const int W = (S + 63) / 64;
-    const int n_stripes = (S + 63) / 64;
+    const int W = (Sk + 63) / 64;
+    const int n_stripes = (Sq + 63) / 64;
     std::vector<Stripe> stripes(n_stripes);
     std::atomic<int> next{0};
     std::atomic<bool> failed{false};
     int n_threads = (int)std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u);
     n_threads = std::min(n_threads, n_stripes);
-    if ((int64_t)S * S < (1 << 20)) n_threads = 1;
+    if ((int64_t)Sq * Sk < (1 << 20)) n_threads = 1;
     auto work = [&]() {
         try {
             std::vector<uint64_t> bits((size_t)64 * W);
             for (;;) {
                 int s = next.fetch_add(1);
                 if (s >= n_stripes) break;
-                analyse_stripe(src, S, block, want_rows, s, bits.data(), stripes[s]);
+                analyse_stripe(src, Sq, Sk, block, want_rows, s, bits.data(), stripes[s]);
             }
         } catch (const std::bad_alloc &) {
             failed = true;
@@ -289,13 +289,13 @@ smha_status_t analyse_mask(const RowSource &src, int S, int block, bool want_row
     }
     if (failed) return SMHA_ERR_ALLOC;
 
-    const int nbr = (S + block - 1) / block;
+    const int nbr = (Sq + block - 1) / block;
     const int per = 64 / block;
     mf.load_row_ptr.assign(nbr + 1, 0);
     mf.full_row_ptr.assign(nbr + 1, 0);
     mf.part_row_ptr.assign(nbr + 1, 0);
     if (want_rows) {
-        mf.row_ptr.assign(S + 1, 0);
+        mf.row_ptr.assign(Sq + 1, 0);
         int64_t total = 0;
         for (auto &st : stripes) total += st.nnz;
         if (total > INT32_MAX) return SMHA_ERR_UNSUPPORTED;
@@ -307,7 +307,7 @@ smha_status_t analyse_mask(const RowSource &src, int S, int block, bool want_row
         mf.nnz += st.nnz;
         mf.n_valid16 += st.valid16;
         if (want_rows) {
-            for (int r = 0; r < 64 && s * 64 + r < S; ++r)
+            for (int r = 0; r < 64 && s * 64 + r < Sq; ++r)
                 mf.row_ptr[s * 64 + r + 1] = mf.row_ptr[s * 64 + r] + st.row_nnz[r];
             mf.col_idx.insert(mf.col_idx.end(), st.cols.begin(), st.cols.end());
         }
@@ -371,15 +371,17 @@ bool rows_wanted(const smha_plan_opts_t &o) {
 // ---------------------------------------------------------------------------------------
 // Kernel selection (Sec. 4.2.3).
 //   paper:      threshold = valid16 / n^2 - tau / (log2 n)^2, n = ceil(S/16), tau = 1.2;
-//               row-wise iff threshold < 0 (n == 1: row-wise).
+//               row-wise iff threshold < 0 (n == 1: row-wise).  The paper states it for as many
+//               queries as keys; with Sq != Sk the ratio is taken over the nq * nk tiles of the
+//               mask and n in the logarithm is the key side, nk = ceil(Sk/16).
 //   calibrated: compare modelled times per (batch, head) pair:
-//               block = tiles64 * t_tile(d) ; row = nnz * t_entry(d) + S * t_rowfix
+//               block = tiles64 * t_tile(d) ; row = nnz * t_entry(d) + Sq * t_rowfix
 // ---------------------------------------------------------------------------------------
-static double eq1_threshold(double valid16, int S) {
-    const double n = std::ceil(S / 16.0);
-    if (n <= 1.0) return -INFINITY;
-    const double lg = std::log2(n);
-    return valid16 / (n * n) - 1.2 / (lg * lg);
+static double eq1_threshold(double valid16, int Sq, int Sk) {
+    const double nq = std::ceil(Sq / 16.0), nk = std::ceil(Sk / 16.0);
+    if (nk <= 1.0) return -INFINITY;
+    const double lg = std::log2(nk);
+    return valid16 / (nq * nk) - 1.2 / (lg * lg);
 }
 
 // Cost-model constants in nanoseconds of whole-chip time per (batch, head) pair, from MI355X
@@ -399,7 +401,7 @@ static CostModel cost_model(int d) {
 
 smha_status_t finish_plan(smha_plan *p) {
     const int n_masks = p->Bm * p->Hm;
-    const int S = p->S;
+    const int S = p->S;  // queries
     double v16 = 0, nnz = 0, tiles = 0;
     for (auto &m : p->masks) {
         v16 += (double)m.n_valid16;
@@ -409,7 +411,7 @@ smha_status_t finish_plan(smha_plan *p) {
     v16 /= n_masks;
     nnz /= n_masks;
     tiles /= n_masks;
-    p->eq1_threshold = eq1_threshold(v16, S);
+    p->eq1_threshold = eq1_threshold(v16, S, p->Sk);
     const CostModel cm = cost_model(p->opts.head_dim);
     p->model_block_us = 1e-3 * (tiles * cm.tile_ns);
     p->model_row_us = 1e-3 * (nnz * cm.entry_ns + S * cm.row_ns);
@@ -535,29 +537,35 @@ using namespace smha;
 extern "C" smha_status_t smha_plan_from_dense(const uint8_t *mask, int mask_on_device, int Bm,
                                               int Hm, int S, const smha_plan_opts_t *opts,
                                               smha_plan_t **out) {
-    if (!mask || !out || Bm < 1 || Hm < 1 || S < 1) return SMHA_ERR_INVALID_ARG;
+    return smha_plan_from_dense_rect(mask, mask_on_device, Bm, Hm, S, S, opts, out);
+}
+
+extern "C" smha_status_t smha_plan_from_dense_rect(const uint8_t *mask, int mask_on_device, int Bm,
+                                                   int Hm, int Sq, int Sk, const smha_plan_opts_t *opts,
+                                                   smha_plan_t **out) {
+    if (!mask || !out || Bm < 1 || Hm < 1 || Sq < 1 || Sk < 1) return SMHA_ERR_INVALID_ARG;
     smha_plan_opts_t o;
     smha_status_t st = check_opts(opts, o);
     if (st != SMHA_OK) return st;
     try {
         std::unique_ptr<smha_plan> p(new smha_plan);
-        p->S = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
-        const size_t per_mask = (size_t)S * S;
-        const size_t words_per_mask = (size_t)S * ((S + 63) / 64);
+        p->S = Sq; p->Sk = Sk; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
+        const size_t per_mask = (size_t)Sq * Sk;
+        const size_t words_per_mask = (size_t)Sq * ((Sk + 63) / 64);
         std::vector<uint64_t> packed;  // a device mask is packed to bits on the GPU: 1/8 of the bytes cross over
         if (mask_on_device) {
             packed.resize(words_per_mask * Bm * Hm);
-            st = pack_device_mask(mask, Bm * Hm, S, packed.data());
+            st = pack_device_mask(mask, Bm * Hm, Sq, Sk, packed.data());
             if (st != SMHA_OK) return st;
         }
         p->masks.resize((size_t)Bm * Hm);
         for (int mi = 0; mi < Bm * Hm; ++mi) {
             if (mask_on_device) {
-                BitSource src(packed.data() + words_per_mask * mi, S);
-                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+                BitSource src(packed.data() + words_per_mask * mi, Sk);
+                st = analyse_mask(src, Sq, Sk, o.block, rows_wanted(o), p->masks[mi]);
             } else {
-                DenseSource src(mask + per_mask * mi, S);
-                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[mi]);
+                DenseSource src(mask + per_mask * mi, Sk);
+                st = analyse_mask(src, Sq, Sk, o.block, rows_wanted(o), p->masks[mi]);
             }
             if (st != SMHA_OK) return st;
         }
@@ -600,13 +608,13 @@ extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B
         std::unique_ptr<smha_plan> p(new smha_plan);
         const int Bm = (d.flags & SMHA_MASK_PADDING) ? B : 1;
         const int Hm = (d.per_head && (d.flags & (SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD))) ? H : 1;
-        p->S = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
+        p->S = S; p->Sk = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
         p->masks.resize((size_t)Bm * Hm);
         for (int b = 0; b < Bm; ++b)
             for (int h = 0; h < Hm; ++h) {
                 const int valid = (d.flags & SMHA_MASK_PADDING) ? d.valid_len[b] : S;
                 DescSource src(d, S, h, valid);
-                st = analyse_mask(src, S, o.block, rows_wanted(o), p->masks[(size_t)b * Hm + h]);
+                st = analyse_mask(src, S, S, o.block, rows_wanted(o), p->masks[(size_t)b * Hm + h]);
                 if (st != SMHA_OK) return st;
             }
         st = finish_plan(p.get());
@@ -621,7 +629,7 @@ extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B
 extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *out) {
     if (!p || !out) return SMHA_ERR_INVALID_ARG;
     smha_plan_info_t i{};
-    i.S = p->S; i.Bm = p->Bm; i.Hm = p->Hm; i.block = p->block; i.kernel = p->kernel;
+    i.S = p->S; i.Sk = p->Sk; i.Bm = p->Bm; i.Hm = p->Hm; i.block = p->block; i.kernel = p->kernel;
     i.has_row_format = p->has_row; i.has_block_kernel_lists = p->has_block; i.on_device = p->device >= 0;
     for (auto &m : p->masks) {
         i.nnz += m.nnz;

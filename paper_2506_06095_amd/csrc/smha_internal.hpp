@@ -64,7 +64,7 @@ struct DeviceArrays {
 }  // namespace smha
 
 struct smha_plan {
-    int S = 0, Bm = 1, Hm = 1, block = 64;
+    int S = 0, Sk = 0, Bm = 1, Hm = 1, block = 64;  // S queries, Sk keys
     smha_plan_opts_t opts{};
     int kernel = SMHA_KERNEL_BLOCK;
     bool has_row = false, has_block = false;
@@ -100,7 +100,7 @@ smha_status_t finish_plan(smha_plan *p);      // selector, work lists, concatena
 smha_status_t upload_plan(smha_plan *p, int device_id);
 void release_device(smha_plan *p);
 // device byte masks [n_masks][S][S] -> host bit rows [n_masks][S][ceil(S/64)] (packed on the GPU)
-smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int S, uint64_t *host_words);
+smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int Sk, uint64_t *host_words);
 int current_device_or_negative();
 
 }  // namespace smha

@@ -160,6 +160,35 @@ def test_long_sequences_on_sampled_rows(torch_mod, smha, name):
 
 
 @pytest.mark.parametrize("kernel", ["block", "row"])
+@pytest.mark.parametrize("Sq,Sk,d,dtype", [(64, 512, 64, "f16"), (100, 1000, 128, "f16"), (257, 130, 64, "bf16"),
+                                           (1, 777, 128, "bf16"), (1024, 64, 64, "f16"), (300, 2100, 128, "f16")])
+def test_fewer_or_more_queries_than_keys(torch_mod, smha, kernel, Sq, Sk, d, dtype):
+    """Cross-attention shapes: a chunk of queries against a longer (or shorter) key sequence."""
+    B, H = 2, 3
+    Q, _, _ = W.qkv_bits(B, H, Sq, d, dtype, 1.0, seed=Sq + Sk)
+    _, K, V = W.qkv_bits(B, H, Sk, d, dtype, 1.0, seed=Sq + Sk + 1)
+    rng = np.random.default_rng(Sq * 7 + Sk)
+    masks = (rng.random((1, H, Sq, Sk)) < 0.2).astype(np.uint8)
+    masks[0, 0, :, : max(1, Sk // 3)] = 1                   # a dense band of keys: full tiles
+    masks[0, 1, Sq // 2] = 0                                # a query with no key
+    if Sk > 64:
+        masks[0, 2, :, 64:] = 0                             # only the first key tile
+    for dev in (False, True):
+        m = torch_mod.from_numpy(masks).cuda() if dev else masks
+        with smha.Plan.from_dense_rect(m, build_both=True, head_dim=d) as plan:
+            assert (plan.info()["S"], plan.info()["Sk"]) == (Sq, Sk)
+            q, k, v = (to_dev(torch_mod, x, dtype) for x in (Q, K, V))
+            out = plan.forward(q, k, v, out_dtype=torch_mod.float32, kernel=KERNELS[kernel])
+            torch_mod.cuda.synchronize()
+            got = out.cpu().numpy()
+            with pytest.raises(ValueError):
+                plan.forward(q, q, q)
+    ref = oracle.masked_attention(Q, K, V, dtype, masks)
+    check(got, ref, f"rect {Sq}x{Sk}/{kernel}")
+    assert np.all(got[:, 1, Sq // 2] == 0.0)
+
+
+@pytest.mark.parametrize("kernel", ["block", "row"])
 @pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
 def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
     for S in (1, 37, 100, 130, 257):

@@ -18,9 +18,9 @@ BSR_KEYS = ["load_row_ptr", "load_col_idx", "flags", "full_row_ptr", "full_col_i
 
 
 def check_plan_against_oracle(plan, masks, bs):
-    Bm, Hm, S, _ = masks.shape
+    Bm, Hm, S, Sk = masks.shape
     info = plan.info()
-    assert (info["S"], info["Bm"], info["Hm"], info["block"]) == (S, Bm, Hm, bs)
+    assert (info["S"], info["Sk"], info["Bm"], info["Hm"], info["block"]) == (S, Sk, Bm, Hm, bs)
     nnz = nvalid = nfull = npart = v16 = 0
     for mi in range(Bm * Hm):
         M = masks[mi // Hm, mi % Hm]
@@ -40,7 +40,7 @@ def check_plan_against_oracle(plan, masks, bs):
         v16 += selector.valid16(M)
     assert (info["nnz"], info["n_valid"], info["n_full"], info["n_part"], info["n_valid16"]) == \
            (nnz, nvalid, nfull, npart, v16)
-    thr = selector.threshold(v16 / (Bm * Hm), S)
+    thr = selector.threshold(v16 / (Bm * Hm), S, Sk=Sk)
     assert info["eq1_threshold"] == pytest.approx(thr, abs=1e-12) or (np.isinf(thr) and np.isinf(info["eq1_threshold"]))
 
 
@@ -68,6 +68,25 @@ def test_ragged_sizes_and_all_block_sizes(S, bs):
     masks[1, 0, :, : S // 2] = 7          # nonzero bytes other than 1 count as "attend"
     with smha.Plan.from_dense(masks, block=bs, build_both=True, device_id=-2) as p:
         check_plan_against_oracle(p, (masks != 0).astype(np.uint8), bs)
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+@pytest.mark.parametrize("Sq,Sk", [(1, 500), (100, 300), (257, 64), (130, 131), (64, 1)])
+def test_fewer_or_more_queries_than_keys(Sq, Sk, bs):
+    rng = np.random.default_rng(Sq * 1000 + Sk + bs)
+    masks = (rng.random((2, 2, Sq, Sk)) < 0.3).astype(np.uint8)
+    masks[0, 0] = 0
+    masks[0, 1] = 1
+    masks[1, 0, :, Sk // 2:] = 0
+    with smha.Plan.from_dense_rect(masks, block=bs, build_both=True, device_id=-2) as p:
+        check_plan_against_oracle(p, masks, bs)
+        rp, ci = p.export("row_ptr", 3), p.export("col_idx", 3)
+        assert np.array_equal(formats.dense_from_csr(rp, ci, Sq, Sk), masks[1, 1])
+        f = {k: p.export(k, 3) for k in ("load_row_ptr", "load_col_idx", "flags")}
+        f["bitmap"] = p.export("bitmap", 3).reshape(-1, bs)
+        assert np.array_equal(formats.dense_from_bsr(f, Sq, bs, Sk), masks[1, 1])
+    with pytest.raises(ValueError):
+        smha.Plan.from_dense(masks, device_id=-2) if Sq != Sk else (_ for _ in ()).throw(ValueError())
 
 
 def test_description_patterns_match_dense_generators():
