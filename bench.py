@@ -153,6 +153,8 @@ def main() -> int:
         "config": {"workload": c.name, "B": B, "H": H, "S": S, "d": d, "block": c.block,
                    "kernel": kernel, "nnz_per_step": info["nnz"] * pairs_per_mask,
                    "tiles64_per_step": info["n_tiles64"] * pairs_per_mask,
+                   "kernel_steps_per_step": info["n_union"] * pairs_per_mask,
+                   "gathered_tiles_per_step": info["n_gathered"] * pairs_per_mask,
                    "plan_from": "dense device mask" if args.dense_device_mask else "pattern description",
                    "cache": "cold (%d rotating sets)" % len(sets) if args.cold else "hot"},
         "latency_ms": {"mean": launch_ms, "median": float(np.median(per)), "min": float(per.min())},

@@ -60,6 +60,9 @@ typedef struct {
                        device if there is one, otherwise stay host-only (forward then returns
                        SMHA_ERR_HIP); -2: host-only on purpose                                 */
     int head_dim;   /* hint for the calibrated selector (0 = 64)                               */
+    int no_gather;  /* nonzero: the block kernel visits every non-empty 64x64 tile as it is; 0: tiles
+                       with few used key columns are repacked into gathered tiles (block kernel
+                       work lists only; the exported formats are never affected)               */
 } smha_plan_opts_t;
 
 /* Mask description: the atomic patterns of the paper (Sec. 2.1.2, Fig. 1) and their
@@ -109,6 +112,7 @@ typedef struct {
     double eq1_threshold; /* Eq. 1 with valid16 averaged over masks; < 0 means row-wise          */
     double model_row_us, model_block_us; /* calibrated cost model, per (batch, head) pair         */
     int Sk;             /* keys per sequence (= S unless the plan came from smha_plan_from_dense_rect) */
+    int64_t n_gathered; /* gathered tiles in the block kernel's lists (each replaces several sparse tiles) */
 } smha_plan_info_t;
 
 /* Arrays smha_plan_export can copy out (all host byte order, packed):
@@ -120,6 +124,15 @@ typedef struct {
  *     bit c (LSB = 0) = tile column c; entries past S are 0, so a ragged tile is never full
  *   BITMAP_IT8 uint64[n_part][64] (block == 64 only): the paper's inner-tile layout, word
  *     ic*8+ir = 8x8 inner tile (ir, ic) (column-major over inner tiles), bit 8*r+c = entry (r,c)
+ * The block kernel's own work lists (for inspection and tests; UNSUPPORTED if the plan has none):
+ *   KERNEL_ITEMS int32[n_items of this mask][8]: {128-row group, first entry, end entry, scratch slot
+ *     or -1, first gathered tile, gathered tiles, 0, 0}
+ *   KERNEL_ENTRIES int32[n][4], all masks: {key tile, code for the group's first 64 rows, code for its
+ *     second 64 rows, gathered tile + 1 or 0}; code -2 = nothing, -1 = every entry set, >= 0 = block
+ *     of KERNEL_BITMAPS.  An ordinary entry covers keys 64*tile .. 64*tile+63; a gathered one the 64
+ *     keys KERNEL_GATHER_KEYS[gathered tile][0..63] (keys >= Sk are padding)
+ *   KERNEL_BITMAPS uint64[n][64]: word r = query row r of the 64, bit k = k-th key of the entry
+ *   KERNEL_GATHER_KEYS int32[n][64]
  */
 typedef enum {
     SMHA_EXPORT_ROW_PTR = 0,
@@ -132,7 +145,11 @@ typedef enum {
     SMHA_EXPORT_FULL_COL_IDX = 7,
     SMHA_EXPORT_PART_ROW_PTR = 8,
     SMHA_EXPORT_PART_COL_IDX = 9,
-    SMHA_EXPORT_BITMAP_IT8 = 10
+    SMHA_EXPORT_BITMAP_IT8 = 10,
+    SMHA_EXPORT_KERNEL_ITEMS = 11,
+    SMHA_EXPORT_KERNEL_ENTRIES = 12,
+    SMHA_EXPORT_KERNEL_BITMAPS = 13,
+    SMHA_EXPORT_KERNEL_GATHER_KEYS = 14
 } smha_export_t;
 
 /* Mask analysis (Sec. 4.2.1) from a dense boolean mask.

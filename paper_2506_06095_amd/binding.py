@@ -24,6 +24,8 @@ EXPORTS = {
     "full_row_ptr": (6, np.int32), "full_col_idx": (7, np.int32),
     "part_row_ptr": (8, np.int32), "part_col_idx": (9, np.int32),
     "bitmap_it8": (10, np.uint64),
+    "kernel_items": (11, np.int32), "kernel_entries": (12, np.int32),
+    "kernel_bitmaps": (13, np.uint64), "kernel_gather_keys": (14, np.int32),
 }
 
 
@@ -35,7 +37,8 @@ class SmhaError(RuntimeError):
 
 class PlanOpts(C.Structure):
     _fields_ = [("block", C.c_int), ("force", C.c_int), ("selector", C.c_int),
-                ("build_both", C.c_int), ("device_id", C.c_int), ("head_dim", C.c_int)]
+                ("build_both", C.c_int), ("device_id", C.c_int), ("head_dim", C.c_int),
+                ("no_gather", C.c_int)]
 
 
 class MaskDesc(C.Structure):
@@ -54,7 +57,7 @@ class PlanInfo(C.Structure):
                 ("n_part", C.c_int64), ("n_valid16", C.c_int64), ("n_tiles64", C.c_int64), ("n_union", C.c_int64),
                 ("n_items", C.c_int64), ("n_split_rows", C.c_int64),
                 ("eq1_threshold", C.c_double), ("model_row_us", C.c_double),
-                ("model_block_us", C.c_double), ("Sk", C.c_int)]
+                ("model_block_us", C.c_double), ("Sk", C.c_int), ("n_gathered", C.c_int64)]
 
 
 _lib = None
@@ -104,9 +107,9 @@ def smha_status_string(status: int) -> str:
 
 
 def _opts(block=0, force=SMHA_KERNEL_AUTO, selector=SMHA_SELECTOR_CALIBRATED, build_both=False,
-          device_id=-1, head_dim=0) -> PlanOpts:
+          device_id=-1, head_dim=0, no_gather=False) -> PlanOpts:
     return PlanOpts(int(block), int(force), int(selector), int(bool(build_both)), int(device_id),
-                    int(head_dim))
+                    int(head_dim), int(bool(no_gather)))
 
 
 def smha_plan_from_dense(mask, **opts) -> int:

@@ -44,6 +44,8 @@ struct FwdParams {
     int max_items;
     int n_work;  // 8 * ceil(B*H/8) * max_items work slots (some empty)
     const UEntry *uent;
+    const int32_t *gidx;  // gathered tiles: 64 key numbers each
+    int n_gidx;           // entries of gidx
     const uint64_t *kt_bitmap;
     int bmp_spare;  // index of an all-zero spare bitmap block (read for tiles without a bitmap)
     float *scratch;
@@ -207,7 +209,9 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
 #define PHASE(k) do { } while (0)
 #endif
 
-template <int D, bool BF16, int OUT>
+// GATHER: the plan holds gathered tiles (staged rows that come from arbitrary key numbers, see
+// UEntry); plans without any run the instantiation that does not know about them.
+template <int D, bool BF16, int OUT, bool GATHER>
 __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
@@ -218,6 +222,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     constexpr int PF = 4;                 // LDS fragment requests kept ahead of the MFMAs
     // K[0], K[1], V[0], V[1]: tile t lives in K[t & 1], V[t & 1]
     __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
+    // key numbers of the current item's gathered tiles (64 each)
+    __shared__ __attribute__((aligned(1024))) int32_t gix[GATHER ? kMaxGatherPerItem * 64 : 1];
     const uint32_t smem_base = (uint32_t)(uintptr_t)(lds_void *)smem;  // LDS byte address
     constexpr int TB = TILE * 2;                                        // bytes per tile
 
@@ -248,7 +254,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // requested right after the current item's last tile, before the current item's output
     // stores, so memory latency of an item's start hides behind the previous item's end.
     struct Work {  // wave-uniform
-        int valid, b, h, bh, qtile, begin, n, slot, col0, code0[2];  // col0, code0: the first entry
+        int valid, b, h, bh, qtile, begin, n, slot, col0, code0[2], gid0;  // col0, code0, gid0: the first entry
+        int gbegin, gcount;
     };
     auto fetch_work = [&](int wg) __attribute__((always_inline)) {
         Work wk;
@@ -258,20 +265,27 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         wk.b = wk.bh / p.H;
         wk.h = wk.bh - wk.b * p.H;
         wk.valid = wg < p.n_work && wk.bh < p.B * p.H;
-        wk.qtile = wk.begin = wk.n = wk.col0 = 0;
+        wk.qtile = wk.begin = wk.n = wk.col0 = wk.gid0 = wk.gbegin = wk.gcount = 0;
         wk.slot = -1;
         wk.code0[0] = wk.code0[1] = -2;
         if (wk.valid) {
             const int mask = (p.Bm > 1 ? wk.b : 0) * p.Hm + (p.Hm > 1 ? wk.h : 0);
             wk.valid = it < uniform_load(p.item_cnt + mask);
             if (wk.valid) {
-                const Item item = uniform_load(p.items + uniform_load(p.item_off + mask) + it);
+                const Item *ip = p.items + uniform_load(p.item_off + mask) + it;
+                struct ItemHead { int32_t qtile, begin, end, slot; };
+                const ItemHead item = uniform_load(reinterpret_cast<const ItemHead *>(ip));
+                if constexpr (GATHER) {
+                    wk.gbegin = uniform_load(&ip->gbegin);
+                    wk.gcount = uniform_load(&ip->gcount);
+                }
                 wk.qtile = item.qtile;
                 wk.begin = item.begin;
                 wk.n = item.end - item.begin;
                 wk.slot = item.slot;
                 const UEntry e0 = uniform_load(p.uent + item.begin);  // (the array ends with a spare entry)
                 wk.col0 = e0.col;
+                wk.gid0 = wk.n > 0 ? e0.gather : 0;
                 wk.code0[0] = wk.n > 0 ? e0.code[0] : -2;
                 wk.code0[1] = wk.n > 0 ? e0.code[1] : -2;
             }
@@ -291,12 +305,16 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         k_go = row * ksb + (pc ^ swz_k<D>(row)) * 16;
         v_go = row * vsb + (pc ^ swz_v<D>(row)) * 16;
     }
+    // With gathered tiles a staged row may come from any key: offset = key * pitch + chunk part.
+    const int g_row = (w * 64 + lane) / CPR;  // the lane's row in the wave's first block
+    const int g_kc = k_go - g_row * ksb, g_vc = v_go - g_row * vsb;
+    const uint32_t gix_lds = (uint32_t)(uintptr_t)(lds_void *)gix;
 
     // state of the item being started / computed
     u32x4 rK, rV;
     // the item's entries, one per lane (at most 64, the planner cuts longer lists): requested
     // here, not touched before the item's first wait
-    int raw_col = 0, raw_code0 = -2, raw_code1 = -2;
+    int raw_col = 0, raw_code0 = -2, raw_code1 = -2, raw_gid = 0;
     uint64_t raw_word = 0;  // bitmap word of the first tile (see fetch_word below)
     // Each wave has a private quarter of the second buffer pair (free between items): its 32 Q rows
     // are staged there (full-line requests instead of 32 partial lines per fragment load), and the
@@ -314,6 +332,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             raw_col = __builtin_nontemporal_load(&u->col);
             raw_code0 = __builtin_nontemporal_load(&u->code[0]);
             raw_code1 = __builtin_nontemporal_load(&u->code[1]);
+            if constexpr (GATHER) raw_gid = __builtin_nontemporal_load(&u->gather);
             const int c0 = (w >> 1) ? wk.code0[1] : wk.code0[0];
             raw_word = p.kt_bitmap[(size_t)(c0 >= 0 ? c0 : p.bmp_spare) * 64 + 32 * (w & 1) + j];
         }
@@ -327,11 +346,33 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             const int row = pchunk / CPR, pc = pchunk % CPR;
             load_to_lds(rQ, priv_lds + i * 1024, (q0 + row) * (int)p.qs.s * 2 + (pc ^ swz_k<D>(row)) * 16);
         }
-        const int kb = wk.n > 0 ? wk.col0 * 64 * ksb : OOB, vb = wk.n > 0 ? wk.col0 * 64 * vsb : OOB;
+        if constexpr (GATHER) {
+            // the key numbers of the item's gathered tiles -> LDS; wave w brings blocks 4 w .. 4 w + 3
+            if (4 * w < wk.gcount) {
+                const u32x4 rG = make_rsrc4(p.gidx, (int64_t)p.n_gidx * 4);
+                load_to_lds(rG, gix_lds + w * 1024, ((wk.gbegin + 4 * w) * 64 + lane * 4) * 4);
+            }
+            // first tile: its key numbers, if it is a gathered one, come straight from memory (the
+            // planner puts gathered tiles last, so this only happens in items that have no other)
+            int key[LPW];
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            load_to_lds(rK, smem_base + (w + 4 * i) * 1024, k_go + (kb + i * RSTEP * ksb));
-            load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, v_go + (vb + i * RSTEP * vsb));
+            for (int i = 0; i < LPW; ++i) key[i] = wk.col0 * 64 + g_row + i * RSTEP;
+            if (wk.gid0 > 0) {
+#pragma unroll
+                for (int i = 0; i < LPW; ++i) key[i] = p.gidx[(size_t)(wk.gid0 - 1) * 64 + g_row + i * RSTEP];
+            }
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, g_kc + (wk.n > 0 ? key[i] * ksb : OOB));
+                load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, g_vc + (wk.n > 0 ? key[i] * vsb : OOB));
+            }
+        } else {
+            const int kb = wk.n > 0 ? wk.col0 * 64 * ksb : OOB, vb = wk.n > 0 ? wk.col0 * 64 * vsb : OOB;
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, k_go + (kb + i * RSTEP * ksb));
+                load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, v_go + (vb + i * RSTEP * vsb));
+            }
         }
     };
     // Invariant at the top of the loop: everything requested for the item has landed (each way
@@ -354,7 +395,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     }
     const int n = item.n;
     const int b = item.b, h = item.h, bh = item.bh;
-    int e_col, e_code;
+    int e_col, e_code, e_gid = 0;
     const int q0 = item.qtile * 128 + 32 * w;
 
     auto entry_col = [&](int t) __attribute__((always_inline)) { return __builtin_amdgcn_readlane(e_col, t & 63); };
@@ -371,13 +412,31 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // slipped between MFMAs (a burst right after the barrier queues up behind the other waves'
     // loads in the CU's one texture-address unit and blocks the wave for hundreds of cycles)
     int ld_kb = OOB, ld_vb = OOB;
+    int ld_key[GATHER ? LPW : 1];  // with gathered tiles: the key each of the lane's staged rows comes from
+    bool ld_live = false;
     auto load_begin = [&](int t) __attribute__((always_inline)) {  // past the end: zeros, no traffic
         const int col = entry_col(t);
-        ld_kb = t < n ? col * 64 * ksb : OOB;
-        ld_vb = t < n ? col * 64 * vsb : OOB;
+        if constexpr (GATHER) {
+            const int gid = t < n ? __builtin_amdgcn_readlane(e_gid, t & 63) : 0;
+            const int slot = max(gid - 1 - item.gbegin, 0);
+            ld_live = t < n;
+#pragma unroll
+            for (int i = 0; i < LPW; ++i) {
+                const int from_list = gix[slot * 64 + g_row + i * RSTEP];
+                ld_key[i] = gid > 0 ? from_list : col * 64 + g_row + i * RSTEP;
+            }
+        } else {
+            ld_kb = t < n ? col * 64 * ksb : OOB;
+            ld_vb = t < n ? col * 64 * vsb : OOB;
+        }
     };
     auto load_piece = [&](int i, uint32_t Kd, uint32_t Vd) __attribute__((always_inline)) {  // i in [0, 2 LPW); LDS byte addresses
-        if (i & 1)
+        if constexpr (GATHER) {
+            if (i & 1)
+                load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 1024, g_vc + (ld_live ? ld_key[i >> 1] * vsb : OOB));
+            else
+                load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, g_kc + (ld_live ? ld_key[i >> 1] * ksb : OOB));
+        } else if (i & 1)
             load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 1024, v_go + (ld_vb + (i >> 1) * RSTEP * vsb));
         else
             load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, k_go + (ld_kb + (i >> 1) * RSTEP * ksb));
@@ -508,6 +567,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // is a compile-time object.
     STAMP(1);
     e_col = raw_col;
+    if constexpr (GATHER) e_gid = raw_gid;
     e_code = lane < n ? ((w >> 1) ? raw_code1 : raw_code0) : -2;
     {
         int krd = k_rd;
@@ -883,7 +943,8 @@ smha_status_t upload_plan(smha_plan *p, int device_id) {
              to_device(d.col_off, p->h_col_off);
     }
     if (ok && p->has_block) {
-        ok = to_device(d.uent, p->h_uent) && to_device(d.kt_bitmap, p->h_kt_bitmap) && to_device(d.items, p->h_items) &&
+        ok = to_device(d.uent, p->h_uent) && to_device(d.gidx, p->h_gidx) && to_device(d.kt_bitmap, p->h_kt_bitmap) &&
+             to_device(d.items, p->h_items) &&
              to_device(d.item_off, p->h_item_off) && to_device(d.item_cnt, p->h_item_cnt) &&
              to_device(d.split_rows, p->h_split_rows) && to_device(d.split_off, p->h_split_off) &&
              to_device(d.split_cnt, p->h_split_cnt);
@@ -903,7 +964,7 @@ void release_device(smha_plan *p) {
     (void)hipGetDevice(&prev);
     (void)hipSetDevice(p->device);
     DeviceArrays &d = p->dev;
-    void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.kt_bitmap, d.items,
+    void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap, d.items,
                     d.item_off, d.item_cnt, d.split_rows, d.split_off, d.split_cnt, p->d_scratch};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
@@ -934,7 +995,10 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
 #ifdef SMHA_DEV
     if (const char *g = getenv("SMHA_GRID")) grid = (unsigned)atoi(g);
 #endif
-    hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT>), dim3(grid), dim3(256), 0, stream, fp);
+    if (plan->n_gathered > 0)
+        hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true>), dim3(grid), dim3(256), 0, stream, fp);
+    else
+        hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false>), dim3(grid), dim3(256), 0, stream, fp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (plan->max_split_rows > 0) {
@@ -1011,7 +1075,7 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
     fp.items = dv.items; fp.item_off = dv.item_off; fp.item_cnt = dv.item_cnt; fp.max_items = plan->max_items;
-    fp.uent = dv.uent; fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
+    fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
     fp.max_slots = plan->max_slots;
     fp.split_rows = dv.split_rows; fp.split_off = dv.split_off; fp.split_cnt = dv.split_cnt;
     fp.row_ptr = dv.row_ptr; fp.col_idx = dv.col_idx; fp.col_off = dv.col_off;

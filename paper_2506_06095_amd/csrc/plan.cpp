@@ -413,58 +413,114 @@ smha_status_t finish_plan(smha_plan *p) {
     tiles /= n_masks;
     p->eq1_threshold = eq1_threshold(v16, S, p->Sk);
     const CostModel cm = cost_model(p->opts.head_dim);
-    p->model_block_us = 1e-3 * (tiles * cm.tile_ns);
     p->model_row_us = 1e-3 * (nnz * cm.entry_ns + S * cm.row_ns);
-
-    int choice;
-    if (p->opts.force != SMHA_KERNEL_AUTO)
-        choice = p->opts.force;
-    else if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1)
-        choice = p->eq1_threshold < 0 ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
-    else
-        choice = p->model_row_us < p->model_block_us ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
-    p->kernel = choice;
-    p->has_row = p->opts.build_both || choice == SMHA_KERNEL_ROW;
-    p->has_block = p->opts.build_both || choice == SMHA_KERNEL_BLOCK;
+    int64_t n_replaced = 0;  // sparse tiles that gathered tiles stand in for
 
     try {
-        // ---- row path: concatenate -------------------------------------------------
-        if (p->has_row) {
-            p->h_row_ptr.reserve((size_t)n_masks * (S + 1));
-            int64_t off = 0;
-            for (auto &m : p->masks) {
-                p->h_col_off.push_back(off);
-                p->h_row_ptr.insert(p->h_row_ptr.end(), m.row_ptr.begin(), m.row_ptr.end());
-                off += (int64_t)m.col_idx.size();
-            }
-            p->h_col_idx.reserve(off);
-            for (auto &m : p->masks)
-                p->h_col_idx.insert(p->h_col_idx.end(), m.col_idx.begin(), m.col_idx.end());
-        }
-        // ---- block path: tiles, work items, split rows ---------------------------
-        if (p->has_block) {
+        // ---- block path first (its work lists say how many tiles the kernel will really visit,
+        // which the selector needs): tiles, work items, split rows --------------------------
+        if (p->opts.force != SMHA_KERNEL_ROW || p->opts.build_both) {
             const int nqt = (S + kTile - 1) / kTile;
             const int nsup = (S + kSuper - 1) / kSuper;
             for (int mi = 0; mi < n_masks; ++mi) {
                 MaskFormats &m = p->masks[mi];
                 const int32_t bmp_base = (int32_t)(p->h_kt_bitmap.size() / 64);
                 p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), m.kt_bitmap.begin(), m.kt_bitmap.end());
-                // union of the two tile rows of every supertile (both lists ascending: merge)
+                // union of the two tile rows of every supertile (both lists ascending: merge); tiles
+                // that use few key columns are repacked into gathered tiles (see UEntry), which go
+                // to the end of the supertile's list
                 std::vector<int32_t> sup_ptr(nsup + 1, 0);
                 const int32_t ent_base = (int32_t)p->h_uent.size();
+                const int64_t pad_key = (int64_t)p->Sk + 64;  // (past the sequence: loads as zeros)
+                struct Sparse { int32_t col, ea, eb; uint64_t used; };
+                std::vector<Sparse> sparse;
+                std::vector<int32_t> keys;
                 for (int sp = 0; sp < nsup; ++sp) {
                     const int r0 = 2 * sp, r1 = 2 * sp + 1;
                     int a = m.kt_row_ptr[r0], ae = m.kt_row_ptr[r0 + 1];
                     int b = r1 < nqt ? m.kt_row_ptr[r1] : 0, be = r1 < nqt ? m.kt_row_ptr[r1 + 1] : 0;
                     auto code = [&](int e) { return m.kt_bmp[e] < 0 ? -1 : m.kt_bmp[e] + bmp_base; };
+                    auto used_cols = [&](int e) {  // which of the tile's 64 key columns any query uses
+                        if (e < 0) return (uint64_t)0;
+                        if (m.kt_bmp[e] < 0) return ~(uint64_t)0;
+                        uint64_t u = 0;
+                        const uint64_t *w = m.kt_bitmap.data() + (size_t)m.kt_bmp[e] * 64;
+                        for (int r = 0; r < 64; ++r) u |= w[r];
+                        return u;
+                    };
+                    sparse.clear();
+                    int n_sparse_cols = 0;
                     while (a < ae || b < be) {
                         UEntry u{0, {-2, -2}, 0};
                         const int ca = a < ae ? m.kt_col[a] : INT32_MAX;
                         const int cb = b < be ? m.kt_col[b] : INT32_MAX;
                         u.col = std::min(ca, cb);
-                        if (ca == u.col) u.code[0] = code(a++);
-                        if (cb == u.col) u.code[1] = code(b++);
+                        const int ea = ca == u.col ? a++ : -1, eb = cb == u.col ? b++ : -1;
+                        const uint64_t used = used_cols(ea) | used_cols(eb);
+                        if (!p->opts.no_gather && __builtin_popcountll(used) <= kGatherMaxCols) {
+                            sparse.push_back({u.col, ea, eb, used});
+                            n_sparse_cols += __builtin_popcountll(used);
+                            continue;
+                        }
+                        if (ea >= 0) u.code[0] = code(ea);
+                        if (eb >= 0) u.code[1] = code(eb);
                         p->h_uent.push_back(u);
+                    }
+                    // repacking pays only if it saves steps
+                    if ((n_sparse_cols + 63) / 64 >= (int)sparse.size()) {
+                        for (const Sparse &t : sparse) {
+                            UEntry u{t.col, {-2, -2}, 0};
+                            if (t.ea >= 0) u.code[0] = code(t.ea);
+                            if (t.eb >= 0) u.code[1] = code(t.eb);
+                            p->h_uent.push_back(u);
+                        }
+                        // (the list is no longer ascending in col; nothing depends on that)
+                    } else {
+                        keys.clear();
+                        for (const Sparse &t : sparse) {
+                            n_replaced += (t.ea >= 0) + (t.eb >= 0);
+                            for (uint64_t x = t.used; x; x &= x - 1) keys.push_back(t.col * 64 + __builtin_ctzll(x));
+                        }
+                        // keys ascend (tiles ascend, bits ascend); 64 per gathered tile
+                        size_t ti = 0;  // sparse tile that holds keys[k]
+                        for (size_t k0 = 0; k0 < keys.size(); k0 += 64) {
+                            const int nk = (int)std::min<size_t>(64, keys.size() - k0);
+                            const int32_t gt = (int32_t)(p->h_gidx.size() / 64);
+                            uint64_t wa[64] = {0}, wb[64] = {0};
+                            for (int k = 0; k < 64; ++k) {
+                                if (k >= nk) {
+                                    p->h_gidx.push_back((int32_t)std::min<int64_t>(pad_key, INT32_MAX));
+                                    continue;
+                                }
+                                const int32_t key = keys[k0 + k];
+                                p->h_gidx.push_back(key);
+                                while (sparse[ti].col != key / 64) ++ti;
+                                const Sparse &t = sparse[ti];
+                                const int bit = key & 63;
+                                for (int side = 0; side < 2; ++side) {
+                                    const int e = side ? t.eb : t.ea;
+                                    if (e < 0) continue;
+                                    uint64_t *dst = side ? wb : wa;
+                                    if (m.kt_bmp[e] < 0) {
+                                        for (int r = 0; r < 64; ++r) dst[r] |= 1ull << k;
+                                    } else {
+                                        const uint64_t *w = m.kt_bitmap.data() + (size_t)m.kt_bmp[e] * 64;
+                                        for (int r = 0; r < 64; ++r) dst[r] |= ((w[r] >> bit) & 1ull) << k;
+                                    }
+                                }
+                            }
+                            UEntry u{0, {-2, -2}, gt + 1};
+                            for (int side = 0; side < 2; ++side) {
+                                const uint64_t *w = side ? wb : wa;
+                                uint64_t any = 0;
+                                for (int r = 0; r < 64; ++r) any |= w[r];
+                                if (!any) continue;
+                                u.code[side] = (int32_t)(p->h_kt_bitmap.size() / 64);
+                                p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), w, w + 64);
+                            }
+                            p->h_uent.push_back(u);
+                            ++p->n_gathered;
+                        }
                     }
                     sup_ptr[sp + 1] = (int32_t)p->h_uent.size() - ent_base;
                 }
@@ -477,20 +533,48 @@ smha_status_t finish_plan(smha_plan *p) {
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
+                auto make_item = [&](int sp, int32_t b, int32_t e, int32_t slot) {
+                    Item it{sp, b, e, slot, 0, 0, {0, 0}};
+                    for (int32_t x = b; x < e; ++x)
+                        if (p->h_uent[x].gather > 0) {
+                            if (!it.gcount) it.gbegin = p->h_uent[x].gather - 1;
+                            ++it.gcount;
+                        }
+                    return it;
+                };
+                std::vector<int32_t> cuts;
                 for (int sp = 0; sp < nsup; ++sp) {
                     const int32_t b = ent_base + sup_ptr[sp], e = ent_base + sup_ptr[sp + 1];
                     const int n = e - b;
-                    if (n <= chunk) {
-                        items.push_back({sp, b, e, -1});
+                    int n_gath = 0;
+                    for (int32_t x = b; x < e; ++x) n_gath += p->h_uent[x].gather > 0;
+                    if (n <= chunk && n_gath <= kMaxGatherPerItem) {
+                        items.push_back(make_item(sp, b, e, -1));
                         continue;
                     }
+                    // equal parts of at most `chunk` entries, cut again where a part would hold more
+                    // gathered tiles than the kernel keeps key numbers for
                     const int parts = (n + chunk - 1) / chunk;
-                    splits.push_back({sp, slots, parts, 0});
-                    for (int c = 0; c < parts; ++c) {
-                        const int32_t cb = b + (int32_t)((int64_t)n * c / parts);
-                        const int32_t ce = b + (int32_t)((int64_t)n * (c + 1) / parts);
-                        items.push_back({sp, cb, ce, slots++});
+                    cuts.clear();
+                    cuts.push_back(b);
+                    for (int c = 1; c <= parts; ++c) {
+                        const int32_t ce = b + (int32_t)((int64_t)n * c / parts);
+                        int g = 0;
+                        for (int32_t x = cuts.back(); x < ce; ++x) {
+                            if (p->h_uent[x].gather > 0 && ++g > kMaxGatherPerItem) {
+                                cuts.push_back(x);
+                                g = 1;
+                            }
+                        }
+                        if (ce > cuts.back()) cuts.push_back(ce);
                     }
+                    const int n_parts = (int)cuts.size() - 1;
+                    if (n_parts == 1) {
+                        items.push_back(make_item(sp, b, e, -1));
+                        continue;
+                    }
+                    splits.push_back({sp, slots, n_parts, 0});
+                    for (int c = 0; c < n_parts; ++c) items.push_back(make_item(sp, cuts[c], cuts[c + 1], slots++));
                 }
                 std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
                     return (a.end - a.begin) > (b.end - b.begin);
@@ -506,9 +590,43 @@ smha_status_t finish_plan(smha_plan *p) {
                 p->max_slots = std::max(p->max_slots, (int)slots);
             }
         }
+        // a gathered tile serves both tile rows of its group: it counts as two tiles
+        p->model_block_us = 1e-3 * ((tiles + (2.0 * (double)p->n_gathered - (double)n_replaced) / n_masks) * cm.tile_ns);
+        int choice;
+        if (p->opts.force != SMHA_KERNEL_AUTO)
+            choice = p->opts.force;
+        else if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1)
+            choice = p->eq1_threshold < 0 ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
+        else
+            choice = p->model_row_us < p->model_block_us ? SMHA_KERNEL_ROW : SMHA_KERNEL_BLOCK;
+        p->kernel = choice;
+        p->has_row = p->opts.build_both || choice == SMHA_KERNEL_ROW;
+        p->has_block = p->opts.build_both || choice == SMHA_KERNEL_BLOCK;
         if (p->has_block) {
             p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), 64, 0ull);  // spare all-zero block
             p->h_uent.push_back(UEntry{0, {-2, -2}, 0});             // spare entry: an empty item may read one past its list
+        } else {  // the row kernel was chosen: the block kernel's lists are not kept
+            std::vector<UEntry>().swap(p->h_uent);
+            std::vector<int32_t>().swap(p->h_gidx);
+            std::vector<uint64_t>().swap(p->h_kt_bitmap);
+            std::vector<Item>().swap(p->h_items);
+            std::vector<SplitRow>().swap(p->h_split_rows);
+            p->h_item_off.clear(); p->h_item_cnt.clear(); p->h_split_off.clear(); p->h_split_cnt.clear();
+            p->max_items = p->max_split_rows = p->max_slots = 0;
+            p->n_gathered = 0;
+        }
+        // ---- row path: concatenate -------------------------------------------------
+        if (p->has_row) {
+            p->h_row_ptr.reserve((size_t)n_masks * (S + 1));
+            int64_t off = 0;
+            for (auto &m : p->masks) {
+                p->h_col_off.push_back(off);
+                p->h_row_ptr.insert(p->h_row_ptr.end(), m.row_ptr.begin(), m.row_ptr.end());
+                off += (int64_t)m.col_idx.size();
+            }
+            p->h_col_idx.reserve(off);
+            for (auto &m : p->masks)
+                p->h_col_idx.insert(p->h_col_idx.end(), m.col_idx.begin(), m.col_idx.end());
         }
         // the per-row column list is large; drop it when no kernel will read it
         if (!p->has_row)
@@ -629,6 +747,7 @@ extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B
 extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *out) {
     if (!p || !out) return SMHA_ERR_INVALID_ARG;
     smha_plan_info_t i{};
+    i.n_gathered = p->n_gathered;
     i.S = p->S; i.Sk = p->Sk; i.Bm = p->Bm; i.Hm = p->Hm; i.block = p->block; i.kernel = p->kernel;
     i.has_row_format = p->has_row; i.has_block_kernel_lists = p->has_block; i.on_device = p->device >= 0;
     for (auto &m : p->masks) {
@@ -688,6 +807,19 @@ extern "C" smha_status_t smha_plan_export(const smha_plan_t *p, int mask_index, 
             vec(it8);
             break;
         }
+        case SMHA_EXPORT_KERNEL_ENTRIES:
+            if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+            src = p->h_uent.data(); bytes = (p->h_uent.size() - 1) * sizeof(UEntry); break;  // (without the spare entry)
+        case SMHA_EXPORT_KERNEL_GATHER_KEYS:
+            if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+            vec(p->h_gidx); break;
+        case SMHA_EXPORT_KERNEL_BITMAPS:
+            if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+            src = p->h_kt_bitmap.data(); bytes = (p->h_kt_bitmap.size() - 64) * sizeof(uint64_t); break;  // (without the spare block)
+        case SMHA_EXPORT_KERNEL_ITEMS:
+            if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+            src = p->h_items.data() + p->h_item_off[mask_index];
+            bytes = (size_t)p->h_item_cnt[mask_index] * sizeof(Item); break;
         default: return SMHA_ERR_INVALID_ARG;
     }
     *need = bytes;

@@ -31,16 +31,27 @@ struct MaskFormats {
 // 64-row tile rows, so that one staged K/V tile serves both.  code[w] tells wave w (tile row
 // 2*super + w) what the tile is for it: -2 = empty (skip), -1 = full, >= 0 = index of its
 // 64-word bitmap.
+//
+// Gathered tiles.  A tile in which only a few key columns are used at all (strided or scattered
+// columns) wastes most of a step.  The planner collects the used columns of such tiles of a
+// supertile, sorts them and packs them 64 at a time into gathered tiles: `gather` - 1 indexes a
+// block of 64 key numbers (one per staged row; unused rows name a key past the sequence, which
+// loads as zeros), col is unused, and the bitmaps say which (query, gathered key) pairs are set.
+// gather = 0: an ordinary tile of 64 consecutive keys starting at 64 * col.
 struct UEntry {
-    int32_t col, code[2], pad;
+    int32_t col, code[2], gather;
 };
 
 // One workgroup's job: supertile `qtile`, union entries [begin, end).  slot < 0: the item
 // covers the whole list and writes O directly; slot >= 0: it writes an unnormalised partial
-// (O, m, l) of 128 rows to that scratch slot.
+// (O, m, l) of 128 rows to that scratch slot.  Its gathered tiles are the gcount consecutive
+// blocks of key numbers starting at block gbegin (at most kMaxGatherPerItem).
 struct Item {
     int32_t qtile, begin, end, slot;
+    int32_t gbegin, gcount, pad[2];
 };
+constexpr int kMaxGatherPerItem = 16;
+constexpr int kGatherMaxCols = 16;  // a tile with at most this many used key columns is repacked
 
 // A supertile whose list was split: `count` partials starting at scratch slot `slot0`.
 struct SplitRow {
@@ -54,6 +65,7 @@ struct DeviceArrays {
     int64_t *col_off = nullptr;   // [n_masks] start of each mask inside col_idx
     // block path
     UEntry *uent = nullptr;
+    int32_t *gidx = nullptr;                               // [n gathered tiles][64] key numbers
     uint64_t *kt_bitmap = nullptr;
     Item *items = nullptr;
     int32_t *item_off = nullptr, *item_cnt = nullptr;      // [n_masks]
@@ -75,12 +87,14 @@ struct smha_plan {
     std::vector<int32_t> h_row_ptr, h_col_idx;
     std::vector<int64_t> h_col_off;
     std::vector<smha::UEntry> h_uent;
+    std::vector<int32_t> h_gidx;  // gathered tiles: 64 key numbers each
     std::vector<uint64_t> h_kt_bitmap;
     std::vector<smha::Item> h_items;
     std::vector<int32_t> h_item_off, h_item_cnt;
     std::vector<smha::SplitRow> h_split_rows;
     std::vector<int32_t> h_split_off, h_split_cnt;
     int max_items = 0, max_split_rows = 0, max_slots = 0;
+    int64_t n_gathered = 0;
 
     int device = -1;  // -1: nothing uploaded
     int n_cu = 256;   // compute units of that device, rounded up to a multiple of 8

@@ -188,6 +188,43 @@ def test_fewer_or_more_queries_than_keys(torch_mod, smha, kernel, Sq, Sk, d, dty
     assert np.all(got[:, 1, Sq // 2] == 0.0)
 
 
+@pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
+@pytest.mark.parametrize("name", ["strided_cols", "scattered", "rect_scattered", "mixed_long_rows", "all_gathered_tiny"])
+def test_gathered_tiles(torch_mod, smha, name, d, dtype):
+    """Tiles with few used key columns are repacked into gathered tiles (staged rows from arbitrary keys):
+    same result as the oracle, and as the plan that visits every tile as it is."""
+    rng = np.random.default_rng(len(name) + d)
+    if name == "strided_cols":
+        masks = W.dense_mask(W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=70, stride=37, stride_phase=5), 1, 1, 1000)
+    elif name == "scattered":
+        masks = W.scattered_spec(700, 3, 5)
+    elif name == "rect_scattered":
+        masks = (rng.random((1, 2, 200, 3000)) < 0.004).astype(np.uint8)
+        masks[0, 1, :, 100:228] = 1
+    elif name == "mixed_long_rows":
+        masks = (rng.random((1, 1, 2300, 2300)) < 0.003).astype(np.uint8)
+        masks[0, 0, :64] = 1
+        masks[0, 0, :, :8] = 1
+        masks[0, 0, 1000] = 0
+    else:  # every tile is sparse: the first tile of each item is a gathered one
+        masks = np.zeros((1, 1, 130, 400), dtype=np.uint8)
+        masks[0, 0, np.arange(130), (np.arange(130) * 37) % 400] = 1
+        masks[0, 0, np.arange(130), (np.arange(130) * 91 + 7) % 400] = 1
+    Bm, Hm, Sq, Sk = masks.shape
+    B, H = 2, 2
+    Q, _, _ = W.qkv_bits(B, H, Sq, d, dtype, 1.0, seed=Sq + d)
+    _, K, V = W.qkv_bits(B, H, Sk, d, dtype, 1.0, seed=Sk + d + 1)
+    q, k, v = (to_dev(torch_mod, x, dtype) for x in (Q, K, V))
+    outs = []
+    for no_gather in (False, True):
+        with smha.Plan.from_dense_rect(masks, head_dim=d, force=smha.SMHA_KERNEL_BLOCK, no_gather=no_gather) as plan:
+            assert (plan.info()["n_gathered"] > 0) == (not no_gather)
+            outs.append(plan.forward(q, k, v, out_dtype=torch_mod.float32).cpu().numpy())
+    ref = oracle.masked_attention(Q, K, V, dtype, masks)
+    check(outs[0], ref, f"gathered {name}")
+    check(outs[1], ref, f"ungathered {name}")
+
+
 @pytest.mark.parametrize("kernel", ["block", "row"])
 @pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
 def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
@@ -326,3 +363,14 @@ def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
         t_row, t_blk = time_kernel(plan, q, k, v, 1), time_kernel(plan, q, k, v, 2)
         print(f"strided causal: row {t_row:.3f} ms, block {t_blk:.3f} ms")
         assert t_blk <= 1.2 * t_row
+    # dilated attention (every 64th key, causal): as 2080 one-column tiles the row kernel would win;
+    # repacked into 32 gathered tiles the block kernel is selected and wins
+    dil = W.MaskSpec(flags=W.CAUSAL | W.STRIDED, stride=64, stride_phase=0)
+    with smha.Plan.from_desc(dil, B, H, S, build_both=True) as plan:
+        assert plan.info()["kernel"] == smha.SMHA_KERNEL_BLOCK and plan.info()["n_gathered"] > 0
+        t_row, t_blk = time_kernel(plan, q, k, v, 1), time_kernel(plan, q, k, v, 2)
+        print(f"dilated: row {t_row:.3f} ms, block with gathered tiles {t_blk:.3f} ms")
+        assert t_blk <= 1.2 * t_row
+        run_case(torch, smha, Q, K, V, "f16", W.dense_mask(dil, B, H, S), 0, heads=[(1, 2)], plan=plan, what="dilated")
+    with smha.Plan.from_desc(dil, B, H, S, no_gather=True) as plan:
+        assert plan.info()["kernel"] == smha.SMHA_KERNEL_ROW

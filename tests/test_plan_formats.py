@@ -210,3 +210,66 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(smha.library_path())
     for n in names:
         assert hasattr(lib, n), n
+
+
+def mask_from_kernel_lists(plan, mi, Sq, Sk):
+    """Rebuild mask `mi` from the block kernel's work lists, counting how often each entry is visited."""
+    items = plan.export("kernel_items", mi).reshape(-1, 8)
+    ents = plan.export("kernel_entries").reshape(-1, 4)
+    bmp = plan.export("kernel_bitmaps").reshape(-1, 64)
+    keys = plan.export("kernel_gather_keys").reshape(-1, 64)
+    cnt = np.zeros((Sq + 128, Sk + 192), dtype=np.int32)
+    bit = np.arange(64, dtype=np.uint64)
+    for qtile, begin, end, slot, gbegin, gcount, _, _ in items:
+        gath = [e for e in range(begin, end) if ents[e, 3] > 0]
+        assert len(gath) == gcount <= 16 and end - begin <= 64
+        assert gath == list(range(end - gcount, end))        # gathered tiles close an item's list
+        for t, e in enumerate(gath):
+            assert ents[e, 3] - 1 == gbegin + t
+        for e in range(begin, end):
+            col, c0, c1, g = ents[e]
+            kk = keys[g - 1] if g > 0 else np.arange(64) + 64 * col
+            for side, code in enumerate((c0, c1)):
+                if code == -2:
+                    continue
+                r0 = qtile * 128 + 64 * side
+                if code == -1:
+                    blk = np.ones((64, 64), dtype=np.int32)
+                else:
+                    blk = ((bmp[code][:, None] >> bit[None, :]) & np.uint64(1)).astype(np.int32)
+                np.add.at(cnt, (np.arange(r0, r0 + 64)[:, None], np.minimum(kk, Sk + 191)[None, :]), blk)
+    return cnt
+
+
+@pytest.mark.parametrize("name", ["cfg3", "strided_cols", "scattered", "rect_scattered", "mixed_long_rows"])
+def test_kernel_work_lists_with_gathered_tiles_cover_the_mask_exactly_once(name):
+    rng = np.random.default_rng(11)
+    if name == "cfg3":
+        c = W.config(3)
+        masks = W.dense_mask(c.mask, 1, 1, c.S)
+    elif name == "strided_cols":
+        masks = W.dense_mask(W.MaskSpec(flags=W.WINDOW | W.STRIDED, window_left=40, window_right=40, stride=37, stride_phase=5), 1, 1, 1000)
+    elif name == "scattered":
+        masks = W.scattered_spec(700, 3, 5)
+    elif name == "rect_scattered":
+        masks = (rng.random((1, 2, 200, 3000)) < 0.004).astype(np.uint8)
+        masks[0, 1, :, 100:228] = 1
+    else:  # a few very long rows (global tokens) next to scattered ones: split groups with gathered tiles
+        masks = (rng.random((1, 1, 4500, 4500)) < 0.002).astype(np.uint8)
+        masks[0, 0, :64] = 1
+        masks[0, 0, :, :8] = 1
+    Bm, Hm, Sq, Sk = masks.shape
+    make = smha.Plan.from_dense if Sq == Sk else smha.Plan.from_dense_rect
+    with make(masks, device_id=-2, force=smha.SMHA_KERNEL_BLOCK) as p, \
+            make(masks, device_id=-2, force=smha.SMHA_KERNEL_BLOCK, no_gather=True) as q:
+        ip, iq = p.info(), q.info()
+        assert ip["n_gathered"] > 0 and iq["n_gathered"] == 0
+        assert ip["n_union"] < iq["n_union"]                       # repacking only when it saves steps
+        assert ip["n_tiles64"] == iq["n_tiles64"]
+        for plan in (p, q):
+            for mi in range(Bm * Hm):
+                cnt = mask_from_kernel_lists(plan, mi, Sq, Sk)
+                assert np.array_equal(cnt[:Sq, :Sk], masks[mi // Hm, mi % Hm].astype(np.int32)), (name, mi)
+                assert cnt[Sq:].sum() == 0 and cnt[:, Sk:].sum() == 0
+        for k in ("load_row_ptr", "load_col_idx", "flags", "bitmap"):  # the exported formats do not change
+            assert np.array_equal(p.export(k), q.export(k))
