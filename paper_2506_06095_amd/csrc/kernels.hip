@@ -475,9 +475,15 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
                 const uint32_t bits = (uint32_t)(word >> (32 * kt)) >> (4 * hh);
+                // two instructions per score: the key's bit spread over a word (0 or all ones), then a
+                // bitwise select between the score and -inf.  (Written on the whole vector: the same
+                // expression element by element was compiled into code that used element 0 for every score.)
+                typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+                u32x16 keep;
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (!((bits >> (8 * (r / 4) + (r % 4))) & 1u)) acc[kt][r] = NEG_INF;
+                for (int r = 0; r < 16; ++r) keep[r] = (uint32_t)__builtin_amdgcn_sbfe((int)bits, 8 * (r / 4) + (r % 4), 1);
+                const u32x16 sc = __builtin_bit_cast(u32x16, acc[kt]);
+                acc[kt] = __builtin_bit_cast(f32x16, (sc & keep) | (~keep & 0xFF800000u));
             }
         }
         // Lazily raised reference: probabilities are formed against the running reference m_run
