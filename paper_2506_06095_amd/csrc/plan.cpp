@@ -360,11 +360,9 @@ smha_status_t check_opts(const smha_plan_opts_t *in, smha_plan_opts_t &o) {
     return SMHA_OK;
 }
 
-// The selector needs tile statistics, so both formats are always *analysed*; the per-row
-// column list is the only large array and is kept only when it can be used.
-bool rows_wanted(const smha_plan_opts_t &o) {
-    return true;  // decided after analysis; see finish_plan (drops col_idx if unused)
-}
+// The per-row column list is the one large array (4 bytes per unmasked entry, written entry by
+// entry): it is built in the first pass only when it will certainly be kept.
+bool rows_wanted(const smha_plan_opts_t &o) { return o.build_both || o.force == SMHA_KERNEL_ROW; }
 
 }  // namespace
 
@@ -397,6 +395,23 @@ struct CostModel {
 static CostModel cost_model(int d) {
     if (d == 128) return {4.0, 0.020, 0.5};
     return {3.4, 0.0134, 0.4};
+}
+
+// After a first pass without the per-row lists: could the selector take the row kernel?  (The
+// block estimate here ignores gathered tiles, so it is an upper bound: if the row kernel does not
+// beat it, it will not beat the final one either.)  If so the masks are analysed again with rows.
+static bool row_may_be_chosen(const smha_plan *p) {
+    if (p->opts.force != SMHA_KERNEL_AUTO) return false;
+    const int n_masks = p->Bm * p->Hm;
+    double v16 = 0, nnz = 0, tiles = 0;
+    for (auto &m : p->masks) {
+        v16 += (double)m.n_valid16;
+        nnz += (double)m.nnz;
+        tiles += (double)m.kt_col.size();
+    }
+    if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1) return eq1_threshold(v16 / n_masks, p->S, p->Sk) < 0;
+    const CostModel cm = cost_model(p->opts.head_dim);
+    return nnz / n_masks * cm.entry_ns + p->S * cm.row_ns < tiles / n_masks * cm.tile_ns;
 }
 
 smha_status_t finish_plan(smha_plan *p) {
@@ -676,17 +691,24 @@ extern "C" smha_status_t smha_plan_from_dense_rect(const uint8_t *mask, int mask
             st = pack_device_mask(mask, Bm * Hm, Sq, Sk, packed.data());
             if (st != SMHA_OK) return st;
         }
-        p->masks.resize((size_t)Bm * Hm);
-        for (int mi = 0; mi < Bm * Hm; ++mi) {
-            if (mask_on_device) {
-                BitSource src(packed.data() + words_per_mask * mi, Sk);
-                st = analyse_mask(src, Sq, Sk, o.block, rows_wanted(o), p->masks[mi]);
-            } else {
-                DenseSource src(mask + per_mask * mi, Sk);
-                st = analyse_mask(src, Sq, Sk, o.block, rows_wanted(o), p->masks[mi]);
+        auto analyse_all = [&](bool rows) {
+            p->masks.assign((size_t)Bm * Hm, MaskFormats{});
+            for (int mi = 0; mi < Bm * Hm; ++mi) {
+                smha_status_t s1;
+                if (mask_on_device) {
+                    BitSource src(packed.data() + words_per_mask * mi, Sk);
+                    s1 = analyse_mask(src, Sq, Sk, o.block, rows, p->masks[mi]);
+                } else {
+                    DenseSource src(mask + per_mask * mi, Sk);
+                    s1 = analyse_mask(src, Sq, Sk, o.block, rows, p->masks[mi]);
+                }
+                if (s1 != SMHA_OK) return s1;
             }
-            if (st != SMHA_OK) return st;
-        }
+            return SMHA_OK;
+        };
+        st = analyse_all(rows_wanted(o));
+        if (st == SMHA_OK && !rows_wanted(o) && row_may_be_chosen(p.get())) st = analyse_all(true);
+        if (st != SMHA_OK) return st;
         st = finish_plan(p.get());
         if (st != SMHA_OK) { release_device(p.get()); return st; }
         *out = p.release();
@@ -727,14 +749,20 @@ extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B
         const int Bm = (d.flags & SMHA_MASK_PADDING) ? B : 1;
         const int Hm = (d.per_head && (d.flags & (SMHA_MASK_BLOCK_RANDOM | SMHA_MASK_BIGBIRD))) ? H : 1;
         p->S = S; p->Sk = S; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
-        p->masks.resize((size_t)Bm * Hm);
-        for (int b = 0; b < Bm; ++b)
-            for (int h = 0; h < Hm; ++h) {
-                const int valid = (d.flags & SMHA_MASK_PADDING) ? d.valid_len[b] : S;
-                DescSource src(d, S, h, valid);
-                st = analyse_mask(src, S, S, o.block, rows_wanted(o), p->masks[(size_t)b * Hm + h]);
-                if (st != SMHA_OK) return st;
-            }
+        auto analyse_all = [&](bool rows) {
+            p->masks.assign((size_t)Bm * Hm, MaskFormats{});
+            for (int b = 0; b < Bm; ++b)
+                for (int h = 0; h < Hm; ++h) {
+                    const int valid = (d.flags & SMHA_MASK_PADDING) ? d.valid_len[b] : S;
+                    DescSource src(d, S, h, valid);
+                    const smha_status_t s1 = analyse_mask(src, S, S, o.block, rows, p->masks[(size_t)b * Hm + h]);
+                    if (s1 != SMHA_OK) return s1;
+                }
+            return SMHA_OK;
+        };
+        st = analyse_all(rows_wanted(o));
+        if (st == SMHA_OK && !rows_wanted(o) && row_may_be_chosen(p.get())) st = analyse_all(true);
+        if (st != SMHA_OK) return st;
         st = finish_plan(p.get());
         if (st != SMHA_OK) { release_device(p.get()); return st; }
         *out = p.release();
