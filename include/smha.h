@@ -154,10 +154,13 @@ typedef enum {
 
 /* Mask analysis (Sec. 4.2.1) from a dense boolean mask.
  *   mask            uint8 [Bm][Hm][S][S], nonzero = attend; host pointer if mask_on_device
- *                   is 0, else a device pointer on the current device (the mask is then
- *                   packed to bit rows by a GPU kernel on the default stream and only those
- *                   cross to the host, where the formats are built; the call synchronises
- *                   before returning)
+ *                   is 0, else a device pointer on the current device.  A device mask is
+ *                   analysed by GPU kernels on the default stream: tile by tile (16 bytes per
+ *                   64x64 tile and the bitmaps of partially filled tiles cross to the host) when
+ *                   the plan needs no per-row lists and exports 64-wide tiles, else packed to bit
+ *                   rows (1/8 of the bytes cross over) for the host analysis.  Either way the
+ *                   plan equals the one built from the same mask in host memory, and the call
+ *                   synchronises before returning
  *   opts            may be NULL (defaults)
  *   out             receives the plan
  * Errors: INVALID_ARG (null, Bm/Hm/S < 1), UNSUPPORTED (block), ALLOC, HIP. */

@@ -919,6 +919,102 @@ smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int
     return SMHA_OK;
 }
 
+// Mask analysis on the device: one wave per 64x64 tile, lane r = row r of the tile.  Reads the
+// dense mask once (HBM-bound), writes 16 bytes per tile and, for partially filled tiles only, the
+// 64 bitmap words (word r = row r, bit c = key column c; entries outside the mask are 0) at a slot
+// taken from a per-mask counter.  Full and empty tiles need no bitmap.
+__global__ void __launch_bounds__(256) smha_mask_classify(const uint8_t *__restrict__ mask, TileInfo *__restrict__ info,
+                                                          uint64_t *__restrict__ part_bits, uint32_t *__restrict__ counters,
+                                                          int Sq, int Sk, int nqt, int nkt, long long n_tiles) {
+    const long long tile = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= n_tiles) return;  // (whole waves leave together)
+    const int lane = threadIdx.x & 63;
+    const long long per_mask = (long long)nqt * nkt;
+    const int mi = (int)(tile / per_mask);
+    const int rem = (int)(tile - mi * per_mask);
+    const int tr = rem / nkt, tc = rem - tr * nkt;
+    const int row = tr * 64 + lane;
+    uint64_t word = 0;
+    if (row < Sq) {
+        const uint8_t *src = mask + ((long long)mi * Sq + row) * Sk + 64ll * tc;
+        const int n = min(64, Sk - 64 * tc);
+        if (n == 64 && ((uintptr_t)src & 15) == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const u32x4 v = reinterpret_cast<const u32x4 *>(src)[q];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t x = v[e];  // any nonzero byte -> its bit 0, then gather the four bit-0s
+                    x |= x >> 4;
+                    x |= x >> 2;
+                    x |= x >> 1;
+                    x &= 0x01010101u;
+                    word |= (uint64_t)((x * 0x10204080u) >> 28) << (16 * q + 4 * e);
+                }
+            }
+        } else {
+            for (int c = 0; c < n; ++c) word |= (uint64_t)(src[c] != 0) << c;
+        }
+    }
+    uint32_t cnt = __builtin_popcountll(word);
+    uint64_t used = word, grp = word;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        cnt += __shfl_xor(cnt, off);
+        used |= __shfl_xor(used, off);
+        if (off < 16) grp |= __shfl_xor(grp, off);  // OR over the 16 rows of the lane's group
+    }
+    uint32_t q16 = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) q16 += ((grp >> (16 * q)) & 0xFFFFull) != 0;
+    const uint32_t v16 = __shfl(q16, 0) + __shfl(q16, 16) + __shfl(q16, 32) + __shfl(q16, 48);
+    uint32_t slot = 0;
+    const bool part = cnt > 0 && cnt < 4096;
+    if (part) {
+        if (lane == 0) slot = atomicAdd(counters + mi, 1u);
+        slot = __shfl(slot, 0);
+        part_bits[((long long)mi * per_mask + slot) * 64 + lane] = word;
+    }
+    if (lane == 0) info[tile] = TileInfo{used, cnt | (v16 << 16), slot};
+}
+
+smha_status_t classify_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int Sk, std::vector<TileInfo> &info,
+                                   std::vector<std::vector<uint64_t>> &part_bits) {
+    const int nqt = (Sq + 63) / 64, nkt = (Sk + 63) / 64;
+    const long long per_mask = (long long)nqt * nkt, n_tiles = per_mask * n_masks;
+    info.resize((size_t)n_tiles);
+    part_bits.assign((size_t)n_masks, {});
+    TileInfo *d_info = nullptr;
+    uint64_t *d_bits = nullptr;
+    uint32_t *d_cnt = nullptr;
+    auto fail = [&](smha_status_t st) {
+        (void)hipGetLastError();
+        (void)hipFree(d_info); (void)hipFree(d_bits); (void)hipFree(d_cnt);
+        return st;
+    };
+    if (hipMalloc(reinterpret_cast<void **>(&d_info), (size_t)n_tiles * sizeof(TileInfo)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&d_bits), (size_t)n_tiles * 512) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void **>(&d_cnt), (size_t)n_masks * 4) != hipSuccess)
+        return fail(SMHA_ERR_ALLOC);
+    if (hipMemsetAsync(d_cnt, 0, (size_t)n_masks * 4, 0) != hipSuccess) return fail(SMHA_ERR_HIP);
+    const unsigned grid = (unsigned)((n_tiles + 3) / 4);
+    hipLaunchKernelGGL(smha_mask_classify, dim3(grid), dim3(256), 0, 0, dev_mask, d_info, d_bits, d_cnt, Sq, Sk, nqt, nkt, n_tiles);
+    if (hipGetLastError() != hipSuccess) return fail(SMHA_ERR_HIP);
+    std::vector<uint32_t> n_part((size_t)n_masks);
+    if (hipMemcpy(info.data(), d_info, (size_t)n_tiles * sizeof(TileInfo), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(n_part.data(), d_cnt, (size_t)n_masks * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(SMHA_ERR_HIP);
+    for (int mi = 0; mi < n_masks; ++mi) {
+        if (!n_part[mi]) continue;
+        part_bits[mi].resize((size_t)n_part[mi] * 64);
+        if (hipMemcpy(part_bits[mi].data(), d_bits + (size_t)mi * per_mask * 64, (size_t)n_part[mi] * 512,
+                      hipMemcpyDeviceToHost) != hipSuccess)
+            return fail(SMHA_ERR_HIP);
+    }
+    (void)hipFree(d_info); (void)hipFree(d_bits); (void)hipFree(d_cnt);
+    return SMHA_OK;
+}
+
 template <typename T>
 static bool to_device(T *&dst, const std::vector<T> &src) {
     dst = nullptr;

@@ -397,6 +397,39 @@ static CostModel cost_model(int d) {
     return {3.4, 0.0134, 0.4};
 }
 
+// Formats of one mask (64-wide tiles, no per-row lists) from what the GPU reported per tile.
+static void formats_from_tiles(const TileInfo *info, const std::vector<uint64_t> &part_bits, int nqt, int nkt,
+                               MaskFormats &mf) {
+    mf = MaskFormats{};
+    mf.load_row_ptr.assign(nqt + 1, 0);
+    mf.full_row_ptr.assign(nqt + 1, 0);
+    mf.part_row_ptr.assign(nqt + 1, 0);
+    for (int tr = 0; tr < nqt; ++tr) {
+        for (int tc = 0; tc < nkt; ++tc) {
+            const TileInfo &t = info[(size_t)tr * nkt + tc];
+            const uint32_t cnt = t.cnt_v16 & 0xFFFFu;
+            mf.nnz += cnt;
+            mf.n_valid16 += (t.cnt_v16 >> 16) & 0xFFu;
+            if (!cnt) continue;
+            const bool full = cnt == 64 * 64;
+            mf.load_col_idx.push_back(tc);
+            mf.flags.push_back(full ? 1 : 0);
+            (full ? mf.full_col_idx : mf.part_col_idx).push_back(tc);
+            if (!full)  // (the GPU stored part tiles in the order its waves reached them: put them in list order)
+                mf.bitmap.insert(mf.bitmap.end(), part_bits.begin() + (size_t)t.slot * 64, part_bits.begin() + (size_t)t.slot * 64 + 64);
+        }
+        mf.load_row_ptr[tr + 1] = (int32_t)mf.load_col_idx.size();
+        mf.full_row_ptr[tr + 1] = (int32_t)mf.full_col_idx.size();
+        mf.part_row_ptr[tr + 1] = (int32_t)mf.part_col_idx.size();
+    }
+    mf.kt_row_ptr = mf.load_row_ptr;  // the kernel's tiles are the exported tiles
+    mf.kt_col = mf.load_col_idx;
+    mf.kt_bmp.resize(mf.flags.size());
+    int32_t part = 0;
+    for (size_t e = 0; e < mf.flags.size(); ++e) mf.kt_bmp[e] = mf.flags[e] ? -1 : part++;
+    mf.kt_bitmap = mf.bitmap;
+}
+
 // After a first pass without the per-row lists: could the selector take the row kernel?  (The
 // block estimate here ignores gathered tiles, so it is an upper bound: if the row kernel does not
 // beat it, it will not beat the final one either.)  If so the masks are analysed again with rows.
@@ -685,8 +718,22 @@ extern "C" smha_status_t smha_plan_from_dense_rect(const uint8_t *mask, int mask
         p->S = Sq; p->Sk = Sk; p->Bm = Bm; p->Hm = Hm; p->block = o.block; p->opts = o;
         const size_t per_mask = (size_t)Sq * Sk;
         const size_t words_per_mask = (size_t)Sq * ((Sk + 63) / 64);
-        std::vector<uint64_t> packed;  // a device mask is packed to bits on the GPU: 1/8 of the bytes cross over
-        if (mask_on_device) {
+        // A device mask whose plan needs neither per-row lists nor tiles narrower than 64 is analysed
+        // by the GPU itself: 16 bytes per tile and the bitmaps of partially filled tiles cross over.
+        bool analysed = false;
+        if (mask_on_device && o.block == 64 && !rows_wanted(o)) {
+            std::vector<TileInfo> info;
+            std::vector<std::vector<uint64_t>> part_bits;
+            st = classify_device_mask(mask, Bm * Hm, Sq, Sk, info, part_bits);
+            if (st != SMHA_OK) return st;
+            const int nqt = (Sq + 63) / 64, nkt = (Sk + 63) / 64;
+            p->masks.assign((size_t)Bm * Hm, MaskFormats{});
+            for (int mi = 0; mi < Bm * Hm; ++mi)
+                formats_from_tiles(info.data() + (size_t)mi * nqt * nkt, part_bits[mi], nqt, nkt, p->masks[mi]);
+            analysed = !row_may_be_chosen(p.get());  // (else: the row kernel may win, which needs the per-row lists)
+        }
+        std::vector<uint64_t> packed;  // otherwise a device mask is packed to bits on the GPU: 1/8 of the bytes cross over
+        if (mask_on_device && !analysed) {
             packed.resize(words_per_mask * Bm * Hm);
             st = pack_device_mask(mask, Bm * Hm, Sq, Sk, packed.data());
             if (st != SMHA_OK) return st;
@@ -706,9 +753,11 @@ extern "C" smha_status_t smha_plan_from_dense_rect(const uint8_t *mask, int mask
             }
             return SMHA_OK;
         };
-        st = analyse_all(rows_wanted(o));
-        if (st == SMHA_OK && !rows_wanted(o) && row_may_be_chosen(p.get())) st = analyse_all(true);
-        if (st != SMHA_OK) return st;
+        if (!analysed) {
+            st = analyse_all(rows_wanted(o));
+            if (st == SMHA_OK && !rows_wanted(o) && row_may_be_chosen(p.get())) st = analyse_all(true);
+            if (st != SMHA_OK) return st;
+        }
         st = finish_plan(p.get());
         if (st != SMHA_OK) { release_device(p.get()); return st; }
         *out = p.release();

@@ -117,6 +117,18 @@ smha_status_t upload_plan(smha_plan *p, int device_id);
 void release_device(smha_plan *p);
 // device byte masks [n_masks][S][S] -> host bit rows [n_masks][S][ceil(S/64)] (packed on the GPU)
 smha_status_t pack_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int Sk, uint64_t *host_words);
+// What the GPU reports about one 64x64 tile of a dense device mask: which of its 64 key columns
+// any query uses, how many entries are set, how many of its sixteen 16x16 sub-tiles are not empty,
+// and, for a partially filled tile, where its 64 bitmap words were put (slot within the mask).
+struct TileInfo {
+    uint64_t used;
+    uint32_t cnt_v16;  // entries set (bits 0-15), non-empty 16x16 sub-tiles (bits 16-23)
+    uint32_t slot;
+};
+// Classifies every tile of n_masks dense masks [Sq][Sk] on the GPU.  info: [mask][tile row][tile col];
+// part_bits[mask]: 64 words per partially filled tile, in slot order.
+smha_status_t classify_device_mask(const uint8_t *dev_mask, int n_masks, int Sq, int Sk,
+                                   std::vector<TileInfo> &info, std::vector<std::vector<uint64_t>> &part_bits);
 int current_device_or_negative();
 
 }  // namespace smha

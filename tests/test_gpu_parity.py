@@ -331,6 +331,47 @@ def test_device_mask_is_packed_on_the_gpu_and_gives_the_host_plan(torch_mod, smh
                     np.testing.assert_array_equal(ph.export(which, mi), pd.export(which, mi), err_msg=f"{which} mask {mi} bs {bs}")
 
 
+@pytest.mark.parametrize("Sq,Sk", [(1, 1), (63, 63), (100, 100), (130, 130), (512, 512), (1000, 1000), (200, 3000), (777, 91)])
+def test_device_mask_is_analysed_on_the_gpu_and_gives_the_host_plan(torch_mod, smha, Sq, Sk):
+    """A device mask whose plan needs no per-row lists (block kernel, 64-wide tiles) is classified tile by tile
+    on the GPU; statistics, exported block format and the kernel's work lists must equal, bit for bit, those
+    of the plan built from the same mask in host memory.  Any nonzero byte means attend."""
+    torch = torch_mod
+    rng = np.random.default_rng(Sq * 3 + Sk)
+    masks = (rng.random((2, 3, Sq, Sk)) < 0.3).astype(np.uint8)
+    masks[masks != 0] = rng.integers(1, 256, size=int(masks.sum()), dtype=np.uint8)
+    masks[1, 2] = 0                                        # an empty mask
+    masks[0, 1, :, : min(Sk, 70)] = 255                    # full tiles
+    masks[1, 0, :, min(Sk - 1, 5)::max(1, Sk // 7)] = 0    # thinned columns
+    masks[1, 1] = 0
+    masks[1, 1, :, ::97] = 1                               # sparse columns: gathered tiles
+    dev = torch.from_numpy(masks).cuda()
+    kw = dict(force=smha.SMHA_KERNEL_BLOCK)
+    with smha.Plan.from_dense_rect(masks, **kw) as ph, smha.Plan.from_dense_rect(dev, **kw) as pd:
+        ih, idv = ph.info(), pd.info()
+        for key in ("S", "Sk", "nnz", "n_valid", "n_full", "n_part", "n_valid16", "n_tiles64", "n_union", "n_items",
+                    "n_gathered", "n_split_rows", "kernel", "eq1_threshold", "model_block_us", "model_row_us"):
+            assert ih[key] == idv[key], key
+        for which in ("kernel_entries", "kernel_bitmaps", "kernel_gather_keys"):
+            np.testing.assert_array_equal(ph.export(which), pd.export(which), err_msg=which)
+        for mi in range(6):
+            for which in ("load_row_ptr", "load_col_idx", "flags", "bitmap", "full_col_idx", "part_row_ptr", "kernel_items"):
+                np.testing.assert_array_equal(ph.export(which, mi), pd.export(which, mi), err_msg=f"{which} mask {mi}")
+        Q, _, _ = W.qkv_bits(2, 3, Sq, 64, "f16", 1.0, seed=Sq)
+        _, K, V = W.qkv_bits(2, 3, Sk, 64, "f16", 1.0, seed=Sk + 1)
+        q, k, v = (to_dev(torch, x, "f16") for x in (Q, K, V))
+        got = pd.forward(q, k, v, out_dtype=torch.float32).cpu().numpy()
+    check(got, oracle.masked_attention(Q, K, V, "f16", (masks != 0).astype(np.uint8)), f"device-analysed {Sq}x{Sk}")
+    # when the selector may take the row kernel the per-row lists are needed: same plan as from the host
+    scat = np.zeros((1, 1, 600, 600), dtype=np.uint8)
+    scat[0, 0, np.arange(600), (np.arange(600) * 131) % 600] = 1
+    scat[0, 0, np.arange(600), (np.arange(600) * 17 + 3) % 600] = 1
+    with smha.Plan.from_dense(scat) as ph, smha.Plan.from_dense(torch.from_numpy(scat).cuda()) as pd:
+        assert ph.info()["kernel"] == pd.info()["kernel"] == smha.SMHA_KERNEL_ROW
+        for which in ("row_ptr", "col_idx"):
+            np.testing.assert_array_equal(ph.export(which), pd.export(which))
+
+
 def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
     """Scattered mask -> the calibrated selector picks row-wise and it is not slower than the
     block kernel there; block-structured mask -> the reverse."""
