@@ -415,3 +415,44 @@ def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
         run_case(torch, smha, Q, K, V, "f16", W.dense_mask(dil, B, H, S), 0, heads=[(1, 2)], plan=plan, what="dilated")
     with smha.Plan.from_desc(dil, B, H, S, no_gather=True) as plan:
         assert plan.info()["kernel"] == smha.SMHA_KERNEL_ROW
+
+
+@pytest.mark.parametrize("case", ["split_rows", "gathered"])
+def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
+    """After one eager call (which sizes the plan's scratch buffer) a forward can be captured into a HIP
+    graph: every replay, with other eager work and synchronisation in between, gives the eager result."""
+    torch = torch_mod
+    if case == "split_rows":    # global block rows make a split 128-row group: main kernel + merge kernel
+        spec = W.MaskSpec(flags=W.BIGBIRD, block=64, n_window_blocks=3, n_global_blocks=2, n_random_blocks=2, seed=9)
+        B, H, S, d = 1, 4, 2048, 128
+    else:
+        spec = W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=100, stride=32, stride_phase=1)
+        B, H, S, d = 2, 2, 1500, 64
+    with smha.Plan.from_desc(spec, B, H, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        info = plan.info()
+        assert (info["n_split_rows"] > 0) if case == "split_rows" else (info["n_gathered"] > 0)
+        gen = torch.Generator(device="cuda").manual_seed(5)
+        q, k, v = (torch.randn(B, H, S, d, device="cuda", generator=gen).half() for _ in range(3))
+        out = torch.empty_like(q)
+        plan.forward(q, k, v, out=out)                      # warm-up: grows the scratch buffer if one is needed
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                plan.forward(q, k, v, out=out)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for t in (q, k, v):
+                t.copy_(torch.randn(B, H, S, d, device="cuda", generator=gen).half())
+            eager = plan.forward(q, k, v)                   # eager work between replays
+            torch.cuda.synchronize()
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), (case, rep)
+        masks = W.dense_mask(spec, B, H, S)
+        Qb, Kb, Vb = (x.cpu().numpy().view(np.uint16) for x in (q, k, v))
+        ref = oracle.masked_attention(*(np.ascontiguousarray(x[:1, :1]) for x in (Qb, Kb, Vb)), "f16", masks)
+        check(out[:1, :1].float().cpu().numpy(), ref, f"graph replay {case}")
