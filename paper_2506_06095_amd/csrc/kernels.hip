@@ -746,11 +746,14 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-template <int D, bool BF16>
+// RPW query rows per wave: 1 (a whole wave per row: long rows) or 4 (16 lanes per row: rows with
+// few keys, where a wave per row spends its time on set-up and on merging 8 mostly idle key groups).
+template <int D, bool BF16, int RPW>
 __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
     constexpr int LPK = D / 8;     // lanes that share one key (16 bytes of the row each)
-    constexpr int KPS = 64 / LPK;  // keys a wave handles per step
-    constexpr int U = 2;           // independent steps in flight
+    constexpr int LPR = 64 / RPW;  // lanes per query row
+    constexpr int KPS = LPR / LPK; // keys a row handles per step
+    constexpr int U = RPW == 1 ? 2 : 4;  // independent steps in flight
     const int wg = blockIdx.x;
     const int xcd = wg & 7, rest = wg >> 3;
     const int grp = rest / p.wgs_per_bh, rb = rest - grp * p.wgs_per_bh;
@@ -759,9 +762,11 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
     const int b = bh / p.H, h = bh - b * p.H;
     const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = rb * 4 + wave;
-    if (i >= p.S) return;
-    const int sub = lane % LPK, g = lane / LPK;
+    const int i_raw = (rb * 4 + wave) * RPW + lane / LPR;
+    if ((rb * 4 + wave) * RPW >= p.S) return;  // (whole waves leave together)
+    const bool row_ok = i_raw < p.S;           // rows past the end stay for the shuffles below, with no keys
+    const int i = row_ok ? i_raw : p.S - 1;
+    const int sub = lane % LPK, g = (lane % LPR) / LPK;
     const float NEG_INF = -__builtin_inff();
 
     float qf[8];
@@ -774,7 +779,7 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
         }
     }
     const int32_t *rp = p.row_ptr + (size_t)mask * (p.S + 1);
-    const int beg = rp[i], end = rp[i + 1];
+    const int beg = rp[i], end = row_ok ? rp[i + 1] : beg;
     const int32_t *ci = p.col_idx + p.col_off[mask];
     const uint16_t *Kb = p.K + b * p.ks.b + h * p.ks.h + 8 * sub;
     const uint16_t *Vb = p.V + b * p.vs.b + h * p.vs.h + 8 * sub;
@@ -826,9 +831,9 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
             }
         }
     }
-    // merge the KPS lane groups (butterfly over lane bits >= LPK)
+    // merge the row's KPS lane groups (butterfly over the lane bits between LPK and LPR)
 #pragma unroll
-    for (int off = LPK; off < 64; off <<= 1) {
+    for (int off = LPK; off < LPR; off <<= 1) {
         const float m_o = __shfl_xor(m, off);
         const float l_o = __shfl_xor(l, off);
         const float m_new = fmaxf(m, m_o);
@@ -839,7 +844,7 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] * wa + __shfl_xor(acc[e], off) * wb;
         m = m_new;
     }
-    if (g == 0) {
+    if (g == 0 && row_ok) {
         const float inv = l > 0.f ? 1.0f / l : 0.f;
         const int64_t o = b * p.os.b + h * p.os.h + (int64_t)i * p.os.s + 8 * sub;
         store_out4(p.O, o, p.out_dtype, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
@@ -1126,9 +1131,15 @@ template <int D, bool BF16>
 static hipError_t launch_row(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     const int BH = fp.B * fp.H;
     const int groups = (BH + 7) / 8;
-    fp.wgs_per_bh = (fp.S + 3) / 4;
+    // rows with few keys share a wave (see the kernel): decided from the mean row length of the plan
+    const bool short_rows = plan->row_mean_nnz <= 32.0;
+    const int rows_per_wg = short_rows ? 16 : 4;
+    fp.wgs_per_bh = (fp.S + rows_per_wg - 1) / rows_per_wg;
     const unsigned grid = (unsigned)(8 * groups * fp.wgs_per_bh);
-    hipLaunchKernelGGL((smha_row_fwd<D, BF16>), dim3(grid), dim3(256), 0, stream, fp);
+    if (short_rows)
+        hipLaunchKernelGGL((smha_row_fwd<D, BF16, 4>), dim3(grid), dim3(256), 0, stream, fp);
+    else
+        hipLaunchKernelGGL((smha_row_fwd<D, BF16, 1>), dim3(grid), dim3(256), 0, stream, fp);
     return hipGetLastError();
 }
 

@@ -388,13 +388,16 @@ static double eq1_threshold(double valid16, int Sq, int Sk) {
 //                 68 us / (64 pairs * 318 tiles) = 3.4 ns per tile at d = 64 (strided causal, S 2048);
 //   row kernel:   232 us / (64 pairs * 269376 entries) = 0.0134 ns per entry at d = 64,
 //                 3.24 ms / (32 pairs * 5.08 M entries) = 0.020 ns per entry at d = 128, and about
-//                 0.4 ns per query row of fixed cost (scattered mask, 9 entries per row: 68 us).
+//                 0.4 ns per query row of fixed cost (a wave per row); rows of at most 32 keys on
+//                 average share a wave four at a time, which cuts that to about a third (scattered
+//                 mask, 9 entries per row, 64 pairs: 68 us with a wave per row, 34-42 us shared).
 struct CostModel {
     double tile_ns, entry_ns, row_ns;
 };
-static CostModel cost_model(int d) {
-    if (d == 128) return {4.0, 0.020, 0.5};
-    return {3.4, 0.0134, 0.4};
+static CostModel cost_model(int d, double mean_row_nnz) {
+    CostModel cm = d == 128 ? CostModel{4.0, 0.020, 0.5} : CostModel{3.4, 0.0134, 0.4};
+    if (mean_row_nnz <= 32.0) cm.row_ns /= 3.0;
+    return cm;
 }
 
 // Formats of one mask (64-wide tiles, no per-row lists) from what the GPU reported per tile.
@@ -443,7 +446,7 @@ static bool row_may_be_chosen(const smha_plan *p) {
         tiles += (double)m.kt_col.size();
     }
     if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1) return eq1_threshold(v16 / n_masks, p->S, p->Sk) < 0;
-    const CostModel cm = cost_model(p->opts.head_dim);
+    const CostModel cm = cost_model(p->opts.head_dim, nnz / n_masks / p->S);
     return nnz / n_masks * cm.entry_ns + p->S * cm.row_ns < tiles / n_masks * cm.tile_ns;
 }
 
@@ -460,8 +463,9 @@ smha_status_t finish_plan(smha_plan *p) {
     nnz /= n_masks;
     tiles /= n_masks;
     p->eq1_threshold = eq1_threshold(v16, S, p->Sk);
-    const CostModel cm = cost_model(p->opts.head_dim);
+    const CostModel cm = cost_model(p->opts.head_dim, nnz / S);
     p->model_row_us = 1e-3 * (nnz * cm.entry_ns + S * cm.row_ns);
+    p->row_mean_nnz = nnz / S;
     int64_t n_replaced = 0;  // sparse tiles that gathered tiles stand in for
 
     try {

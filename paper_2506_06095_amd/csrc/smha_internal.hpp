@@ -84,6 +84,7 @@ struct smha_plan {
     bool has_row = false, has_block = false;
     std::vector<smha::MaskFormats> masks;
     double eq1_threshold = 0.0, model_row_us = 0.0, model_block_us = 0.0;
+    double row_mean_nnz = 0.0;  // unmasked keys per query row, mean over masks
 
     // concatenated host copies of what the kernels read
     std::vector<int32_t> h_row_ptr, h_col_idx;
