@@ -189,7 +189,8 @@ def test_fewer_or_more_queries_than_keys(torch_mod, smha, kernel, Sq, Sk, d, dty
 
 
 @pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "f16"), (64, "bf16"), (128, "bf16")])
-@pytest.mark.parametrize("name", ["strided_cols", "scattered", "rect_scattered", "mixed_long_rows", "all_gathered_tiny"])
+@pytest.mark.parametrize("name", ["strided_cols", "scattered", "rect_scattered", "mixed_long_rows", "all_gathered_tiny",
+                                  "many_gathered"])
 def test_gathered_tiles(torch_mod, smha, name, d, dtype):
     """Tiles with few used key columns are repacked into gathered tiles (staged rows from arbitrary keys):
     same result as the oracle, and as the plan that visits every tile as it is."""
@@ -206,12 +207,14 @@ def test_gathered_tiles(torch_mod, smha, name, d, dtype):
         masks[0, 0, :64] = 1
         masks[0, 0, :, :8] = 1
         masks[0, 0, 1000] = 0
+    elif name == "many_gathered":  # every 5th key: 19 gathered tiles per 128 rows, more than one item may hold
+        masks = W.dense_mask(W.MaskSpec(flags=W.STRIDED, stride=5, stride_phase=2), 1, 1, 6000)
     else:  # every tile is sparse: the first tile of each item is a gathered one
         masks = np.zeros((1, 1, 130, 400), dtype=np.uint8)
         masks[0, 0, np.arange(130), (np.arange(130) * 37) % 400] = 1
         masks[0, 0, np.arange(130), (np.arange(130) * 91 + 7) % 400] = 1
     Bm, Hm, Sq, Sk = masks.shape
-    B, H = 2, 2
+    B, H = (1, 2) if name == "many_gathered" else (2, 2)
     Q, _, _ = W.qkv_bits(B, H, Sq, d, dtype, 1.0, seed=Sq + d)
     _, K, V = W.qkv_bits(B, H, Sk, d, dtype, 1.0, seed=Sk + d + 1)
     q, k, v = (to_dev(torch_mod, x, dtype) for x in (Q, K, V))
@@ -219,6 +222,8 @@ def test_gathered_tiles(torch_mod, smha, name, d, dtype):
     for no_gather in (False, True):
         with smha.Plan.from_dense_rect(masks, head_dim=d, force=smha.SMHA_KERNEL_BLOCK, no_gather=no_gather) as plan:
             assert (plan.info()["n_gathered"] > 0) == (not no_gather)
+            if name == "many_gathered" and not no_gather:
+                assert plan.info()["n_split_rows"] > 0      # lists cut at 16 gathered tiles: partial results merged
             outs.append(plan.forward(q, k, v, out_dtype=torch_mod.float32).cpu().numpy())
     ref = oracle.masked_attention(Q, K, V, dtype, masks)
     check(outs[0], ref, f"gathered {name}")
