@@ -130,8 +130,9 @@ __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dt
 // so swz_v must send those rows to different aligned groups of 4 chunks.  The swizzle is
 // applied on the global side: LDS chunk p of a row is filled with global chunk p ^ swz(row).
 // Rows past S read as zeros (buffer bounds), so ragged S needs no branches.
-// Both tiles are double-buffered: the loads of tile t+2 are issued right after the barrier
-// that ends tile t and are only waited for at the barrier that ends tile t+1.
+// Both tiles are double-buffered: the loads of tile t+1 are issued at the top of tile t (right
+// after the barrier that ends tile t-1 freed their buffers) and are waited for at the barrier
+// that ends tile t.
 //
 // S^T = K Q^T reads K fragments with 16-byte LDS reads (a lane's 8 consecutive d values of
 // one key).  O^T = V^T P^T needs, per lane, 8 keys of one d column: ds_read_b64_tr_b16
@@ -408,9 +409,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         return p.kt_bitmap[(size_t)blk * 64 + 32 * (w & 1) + j];
     };
 
-    // the 2 LPW load instructions of one tile, addressable one at a time so that they can be
-    // slipped between MFMAs (a burst right after the barrier queues up behind the other waves'
-    // loads in the CU's one texture-address unit and blocks the wave for hundreds of cycles)
+    // the wave's 2 LPW load instructions of one tile (K and V pieces alternate)
     int ld_kb = OOB, ld_vb = OOB;
     int ld_key[GATHER ? LPW : 1];  // with gathered tiles: the key each of the lane's staged rows comes from
     bool ld_live = false;
@@ -572,10 +571,12 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         __builtin_amdgcn_s_setprio(0);
     };
 
-    // ---- main loop: tile t is computed from one LDS buffer while the loads of tile t+1 are
-    // issued (between the MFMAs) into the other, which every wave left at the previous barrier;
-    // they are waited for at the barrier that ends tile t.  Unrolled by two so that each buffer
-    // is a compile-time object.
+    // ---- main loop: tile t is computed from one LDS buffer pair while the loads of tile t+1,
+    // issued at the top of the iteration and outside every branch (with the loads inside the
+    // arms of the branch below the compiler keeps the output accumulators in two register sets
+    // and copies between them), land in the other pair, which every wave left at the previous
+    // barrier; they are waited for at the barrier that ends tile t.  One loop body; the buffer
+    // pair is a run-time offset.
     STAMP(1);
     e_col = raw_col;
     if constexpr (GATHER) e_gid = raw_gid;
