@@ -98,8 +98,21 @@ def test_config_4_bf16_full_size(torch_mod, smha, kernel):
     with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, build_both=True, head_dim=c.d) as plan:
         run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], out_f32=True, heads=heads,
                  plan=plan, what=f"{c.name}/{kernel}/f32out")
-        run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], out_f32=False,
-                 heads=[(0, 3)], plan=plan, what=f"{c.name}/{kernel}/bf16out")
+        got = run_case(torch_mod, smha, Q, K, V, c.dtype, masks, KERNELS[kernel], out_f32=False,
+                       heads=[(0, 3)], plan=plan, what=f"{c.name}/{kernel}/bf16out")
+    # bfloat16 output against the oracle rounded to bfloat16 (nearest even): distance in units of the last place
+    m1 = np.ascontiguousarray(masks[0, 3][None, None])
+    ref = oracle.masked_attention(*(np.ascontiguousarray(x[:1, 3:4]) for x in (Q, K, V)), c.dtype, m1)
+
+    def ordered(bits):  # bit patterns -> integers that are monotonic in the value
+        b = bits.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b)
+
+    ulps = np.abs(ordered(W.f64_to_bf16_bits(got[:1, 3:4].astype(np.float64))) - ordered(W.f64_to_bf16_bits(ref)))
+    hist = np.bincount(np.minimum(ulps.ravel(), 4), minlength=5) / ulps.size
+    print(f"{c.name}/{kernel}: bfloat16 output, ulp distance 0/1/2/3/4+ = " + " ".join(f"{x:.4f}" for x in hist))
+    big = np.abs(ref) >= 2.0 ** -6        # (tiny outputs: a unit in the last place is far below the 5e-3 gate)
+    assert hist[0] + hist[1] >= 0.99 and ulps[big].max() <= 2
 
 
 def test_config_5_full_size_sampled_heads(torch_mod, smha):
