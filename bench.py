@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = BigBird, seq 8192)")
     ap.add_argument("--kernel", choices=["auto", "row", "block"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short untimed-region runs of the other configurations")
     ap.add_argument("--cpu-heads", type=int, default=0, help="heads the oracle is timed on (0 = auto)")
     ap.add_argument("--cold", action="store_true",
                     help="rotate over enough Q/K/V/O sets that every step reads from HBM (not the headline)")
@@ -163,6 +165,34 @@ def main() -> int:
         "plan_ms": plan_ms,
         "roofline": roof,
     }
+
+    if not args.no_other_configs:
+        # the other configurations, outside the timed region: latency of the selected kernel (mean of 30 launches)
+        others = {}
+        for idx in (1, 2, 3, 4, 5):
+            if idx == args.config:
+                continue
+            oc = W.config(idx)
+            odt = torch.float16 if oc.dtype == "f16" else torch.bfloat16
+            g = torch.Generator(device="cuda").manual_seed(oc.seed)
+            oq, ok_, ov = (torch.randn(oc.B, oc.H, oc.S, oc.d, device="cuda", generator=g).mul_(oc.std).to(odt) for _ in range(3))
+            oo = torch.empty_like(oq)
+            with smha.Plan.from_desc(oc.mask, oc.B, oc.H, oc.S, block=oc.block, head_dim=oc.d) as op:
+                oi = op.info()
+                for _ in range(5):
+                    op.forward(oq, ok_, ov, out=oo)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(30):
+                    op.forward(oq, ok_, ov, out=oo)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                oms = e0.elapsed_time(e1) / 30
+            onnz = oi["nnz"] * (oc.B * oc.H // (oi["Bm"] * oi["Hm"]))
+            others[oc.name] = {"ms": oms, "kernel": "row" if oi["kernel"] == smha.SMHA_KERNEL_ROW else "block",
+                               "effective_tflops": 4.0 * onnz * oc.d / (oms * 1e-3) / 1e12}
+            del oq, ok_, ov, oo
+        result["other_configs"] = others
 
     if not args.no_cpu_baseline:
         import oracle
