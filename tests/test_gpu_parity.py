@@ -262,6 +262,47 @@ def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
         assert np.allclose(got[1, 1].astype(np.float64), W.bits_to_f64(V, dtype)[1, 1], rtol=1e-5, atol=1e-7)
 
 
+def test_random_shapes_masks_and_sharing(torch_mod, smha):
+    """Seeded sweep over query / key counts around the tile edges, both head sizes and dtypes, masks shared
+    or not across batch and heads, five mask families (unstructured at several densities, 64-blocky, band
+    plus columns, empty and full rows mixed), three block sizes; both kernels, fp32 and 16-bit output."""
+    torch = torch_mod
+    rng = np.random.default_rng(1234)
+    for case in range(48):
+        Sq = int(rng.choice([1, 2, 17, 63, 64, 65, 100, 127, 128, 129, 200, 300, 513]))
+        Sk = Sq if rng.random() < 0.5 else int(rng.choice([1, 5, 64, 65, 130, 257, 700]))
+        d = int(rng.choice([64, 128]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        B, H = int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 5, 9]))
+        Bm, Hm = (B if rng.random() < 0.4 else 1), (H if rng.random() < 0.4 else 1)
+        kind = int(rng.integers(0, 5))
+        dens = float(rng.choice([0.0, 0.02, 0.2, 0.7, 1.0]))
+        m = (rng.random((Bm, Hm, Sq, Sk)) < dens).astype(np.uint8)
+        if kind == 1:
+            blk = (rng.random((Bm, Hm, (Sq + 63) // 64, (Sk + 63) // 64)) < 0.4).astype(np.uint8)
+            m = np.kron(blk, np.ones((64, 64), np.uint8))[:, :, :Sq, :Sk].copy()
+        elif kind == 2:
+            i, j = np.arange(Sq)[:, None], np.arange(Sk)[None, :]
+            m = np.broadcast_to(((np.abs(i - j) <= 20) | (j % 97 == 3)).astype(np.uint8), (Bm, Hm, Sq, Sk)).copy()
+        elif kind == 3:
+            m[:, :, ::3, :] = 0
+            m[:, :, 1::7, :] = 1
+        block = int(rng.choice([16, 32, 64]))
+        Qb, _, _ = W.qkv_bits(B, H, Sq, d, dtype, 1.0, 1000 + case)
+        _, Kb, Vb = W.qkv_bits(B, H, Sk, d, dtype, 1.0, 2000 + case)
+        q, k, v = (to_dev(torch, x, dtype) for x in (Qb, Kb, Vb))
+        ref = oracle.masked_attention(Qb, Kb, Vb, dtype, m, None)
+        what = f"case {case}: B{B} H{H} Sq{Sq} Sk{Sk} d{d} {dtype} Bm{Bm} Hm{Hm} kind{kind} density{dens} block{block}"
+        make = smha.Plan.from_dense if Sq == Sk else smha.Plan.from_dense_rect
+        with make(m, block=block, build_both=True, head_dim=d) as plan:
+            for kernel in KERNELS.values():
+                for f32 in (True, False):
+                    out = plan.forward(q, k, v, out_dtype=torch.float32 if f32 else None, kernel=kernel)
+                    torch.cuda.synchronize()
+                    check(out.float().cpu().numpy(), ref, f"{what} kernel {kernel} fp32 out {f32}",
+                          bf16_out=(dtype == "bf16" and not f32))
+
+
 @pytest.mark.parametrize("bs", [16, 32, 64])
 def test_block_sizes_and_scale_and_same_dtype_output(torch_mod, smha, bs):
     c = W.config(3)
