@@ -710,17 +710,38 @@ __global__ void __launch_bounds__(16 * (D / 4)) smha_block_combine(const FwdPara
     const int row = blockIdx.y * 16 + threadIdx.x / (D / 4), dq = threadIdx.x % (D / 4);
     const int qrow = sr.qtile * 128 + row;
     if (qrow >= p.S) return;
-    float mstar = -__builtin_inff();
-    for (int c = 0; c < sr.count; ++c) mstar = fmaxf(mstar, base[c * stride + 128 * D + row]);
+    // Loads go out in batches of 8 partials, all requested before the first is used: the kernel is
+    // a chain of memory latencies otherwise (partials were written by other XCDs, so they miss L2).
+    constexpr int NB = 8;
+    const float NEG_INF = -__builtin_inff();
+    float mstar = NEG_INF;
+    for (int c0 = 0; c0 < sr.count; c0 += NB) {
+        float ms[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) ms[u] = c0 + u < sr.count ? base[(c0 + u) * stride + 128 * D + row] : NEG_INF;
+#pragma unroll
+        for (int u = 0; u < NB; ++u) mstar = fmaxf(mstar, ms[u]);
+    }
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     float L = 0.f;
-    if (mstar != -__builtin_inff()) {
-#pragma unroll 4
-        for (int c = 0; c < sr.count; ++c) {
-            const float wgt = fast_exp2(base[c * stride + 128 * D + row] - mstar);
-            L += wgt * base[c * stride + 128 * D + 128 + row];
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(base + c * stride + row * D + 4 * dq);
-            acc += v * wgt;
+    if (mstar != NEG_INF) {
+        for (int c0 = 0; c0 < sr.count; c0 += NB) {
+            float ms[NB], ls[NB];
+            f32x4 vs[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const bool live = c0 + u < sr.count;
+                const float *part = base + (live ? c0 + u : c0) * stride;
+                ms[u] = live ? part[128 * D + row] : NEG_INF;  // (weight 0 past the end)
+                ls[u] = part[128 * D + 128 + row];
+                vs[u] = *reinterpret_cast<const f32x4 *>(part + row * D + 4 * dq);
+            }
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const float wgt = fast_exp2(ms[u] - mstar);
+                L += wgt * ls[u];
+                acc += vs[u] * wgt;
+            }
         }
     }
     const float inv = L > 0.f ? 1.0f / L : 0.f;
