@@ -335,7 +335,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             raw_code1 = __builtin_nontemporal_load(&u->code[1]);
             if constexpr (GATHER) raw_gid = __builtin_nontemporal_load(&u->gather);
             const int c0 = (w >> 1) ? wk.code0[1] : wk.code0[0];
-            raw_word = p.kt_bitmap[(size_t)(c0 >= 0 ? c0 : p.bmp_spare) * 64 + 32 * (w & 1) + j];
+            raw_word = 0;
+            if (c0 >= 0) raw_word = p.kt_bitmap[(size_t)c0 * 64 + 32 * (w & 1) + j];
         }
         // Q rows q0 .. q0+31 -> private slab, chunks swizzled like a K tile's (rows past S: zeros)
         const int q0 = wk.qtile * 128 + 32 * w;
@@ -599,7 +600,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     for (int t = 0; t < n; ++t) {
         const int par = t & 1;
         const int code_next = entry_code(t + 1);
-        const uint64_t word_next = fetch_word(code_next);
+        uint64_t word_next = 0;  // (only part tiles have a bitmap; the others never look at the word)
+        if (code_next >= 0) word_next = fetch_word(code_next);
         load_begin(t + 1);
         const uint32_t Kn = smem_base + (par ^ 1) * TB, Vn = smem_base + (2 + (par ^ 1)) * TB;
 #pragma unroll
