@@ -47,7 +47,7 @@ struct FwdParams {
     const int32_t *gidx;  // gathered tiles: 64 key numbers each
     int n_gidx;           // entries of gidx
     const uint64_t *kt_bitmap;
-    int bmp_spare;  // index of an all-zero spare bitmap block (read for tiles without a bitmap)
+    int bmp_spare;  // index of an all-zero spare bitmap block (what fetch_word falls back to for a tile without a bitmap)
     float *scratch;
     int max_slots;
     const SplitRow *split_rows;
@@ -404,7 +404,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     auto entry_code = [&](int t) __attribute__((always_inline)) {
         return t < n ? __builtin_amdgcn_readlane(e_code, t & 63) : -2;
     };
-    // bitmap word of this lane's query row for a part tile; full / empty tiles read a spare block
+    // bitmap word of this lane's query row for a part tile (callers skip full and empty tiles; the
+    // spare block only keeps the index valid if one does not)
     auto fetch_word = [&](int code) __attribute__((always_inline)) {
         const int blk = code >= 0 ? code : p.bmp_spare;
         return p.kt_bitmap[(size_t)blk * 64 + 32 * (w & 1) + j];
