@@ -166,6 +166,8 @@ __device__ __forceinline__ u32x4 make_rsrc4(const void *base, int64_t bytes) {
 // buffers of a pair to be compile-time objects (a loop body per buffer) and adds full waits
 // wherever it cannot tell; here every wait for these loads is an explicit s_waitcnt in the
 // kernel (memory operations retire in order, so the compiler's own vmcnt waits stay safe).
+// M0 is written here without being listed as clobbered: the compiler reserves it, sets it right
+// before each use of its own and rejects it on a clobber list with a warning.
 __device__ __forceinline__ void load_to_lds(u32x4 rsrc, uint32_t lds, int byte_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds), "v"(byte_off), "s"(rsrc) : "memory");
