@@ -205,40 +205,53 @@ def smha_kernel_name(plan: int, d: int, in_dtype: int, kernel: int = SMHA_KERNEL
 
 
 def _strides3(t):
+    """NULL (= packed) for a contiguous tensor, else the three leading strides in elements."""
+    if t.is_contiguous():
+        return None
     st = t.stride()
     if st[3] != 1:
         raise ValueError("head_dim must be contiguous")
     return (C.c_int64 * 3)(st[0], st[1], st[2])
 
 
+_DTYPE_CODES = None
+
+
 def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
-                 stream=None) -> None:
+                 stream=None, _dims=None) -> None:
     """Q, O: torch CUDA tensors [B,H,S,d]; K, V: [B,H,Sk,d] (S and Sk as in the plan); O in the
     input dtype or float32.  Enqueues on `stream` (default: torch's current stream); does not
-    synchronise."""
+    synchronise.  (_dims: the plan's (S, Sk) if the caller already holds them.)"""
     import torch
+    global _DTYPE_CODES
+    if _DTYPE_CODES is None:
+        _DTYPE_CODES = {torch.float16: SMHA_F16, torch.bfloat16: SMHA_BF16, torch.float32: SMHA_F32}
+    lib = _load()
     B, H, S, d = Q.shape
-    info = PlanInfo()
-    st = _load().smha_plan_info(C.c_void_p(plan), C.byref(info))
-    if st != 0:
-        raise SmhaError(st, "smha_plan_info")
+    if _dims is None:
+        info = PlanInfo()
+        st = lib.smha_plan_info(plan, C.byref(info))
+        if st != 0:
+            raise SmhaError(st, "smha_plan_info")
+        _dims = (info.S, info.Sk)
     if O.shape != Q.shape or K.shape != V.shape or K.shape[:2] != Q.shape[:2] or K.shape[3] != d:
         raise ValueError("Q, O must be [B,H,S,d] and K, V [B,H,Sk,d]")
-    if S != info.S or K.shape[2] != info.Sk:
-        raise ValueError(f"the plan is for {info.S} queries and {info.Sk} keys per sequence")
-    codes = {torch.float16: SMHA_F16, torch.bfloat16: SMHA_BF16, torch.float32: SMHA_F32}
-    if Q.dtype not in (torch.float16, torch.bfloat16) or K.dtype != Q.dtype or V.dtype != Q.dtype:
+    if S != _dims[0] or K.shape[2] != _dims[1]:
+        raise ValueError(f"the plan is for {_dims[0]} queries and {_dims[1]} keys per sequence")
+    in_code = _DTYPE_CODES.get(Q.dtype)
+    if in_code is None or in_code == SMHA_F32 or K.dtype != Q.dtype or V.dtype != Q.dtype:
         raise ValueError("Q, K, V must be float16 or bfloat16")
+    out_code = _DTYPE_CODES.get(O.dtype)
+    if out_code is None:
+        raise ValueError("O must be float16, bfloat16 or float32")
     if not (Q.is_cuda and K.is_cuda and V.is_cuda and O.is_cuda):
         raise ValueError("tensors must be on the GPU")
     if stream is None:
         stream = torch.cuda.current_stream(Q.device)
     handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
-    st = _load().smha_forward(C.c_void_p(plan), C.c_void_p(Q.data_ptr()), C.c_void_p(K.data_ptr()),
-                              C.c_void_p(V.data_ptr()), C.c_void_p(O.data_ptr()), B, H, d,
-                              codes[Q.dtype], codes[O.dtype], _strides3(Q), _strides3(K),
-                              _strides3(V), _strides3(O), float(scale), int(kernel),
-                              C.c_void_p(handle))
+    st = lib.smha_forward(plan, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, d,
+                          in_code, out_code, _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
+                          float(scale), int(kernel), handle)
     if st != 0:
         raise SmhaError(st, "smha_forward")
 
@@ -248,6 +261,7 @@ class Plan:
 
     def __init__(self, handle: int):
         self.handle = handle
+        self._dims = None  # (S, Sk), read from the plan at the first forward
 
     @classmethod
     def from_dense(cls, mask, **opts) -> "Plan":
@@ -272,7 +286,10 @@ class Plan:
         import torch
         if out is None:
             out = torch.empty(Q.shape, dtype=out_dtype or Q.dtype, device=Q.device)
-        smha_forward(self.handle, Q, K, V, out, scale, kernel, stream)
+        if self._dims is None:
+            info = self.info()
+            self._dims = (info["S"], info["Sk"])
+        smha_forward(self.handle, Q, K, V, out, scale, kernel, stream, self._dims)
         return out
 
     def close(self) -> None:
