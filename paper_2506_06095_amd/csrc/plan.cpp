@@ -582,6 +582,9 @@ smha_status_t finish_plan(smha_plan *p) {
                 for (int sp = 0; sp < nsup; ++sp) n_nonempty += sup_ptr[sp + 1] > sup_ptr[sp];
                 const double avg = n_nonempty ? (double)sup_ptr[nsup] / n_nonempty : 0.0;
                 const int chunk = std::min(64, std::max(16, (int)std::ceil(1.5 * avg)));  // the kernel holds one entry per lane
+                // lists up to twice that stay whole: merging costs a second launch (4-6 us), more than
+                // a workgroup that runs a few steps longer than the others
+                const int whole = std::min(64, 2 * chunk);
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
@@ -600,7 +603,7 @@ smha_status_t finish_plan(smha_plan *p) {
                     const int n = e - b;
                     int n_gath = 0;
                     for (int32_t x = b; x < e; ++x) n_gath += p->h_uent[x].gather > 0;
-                    if (n <= chunk && n_gath <= kMaxGatherPerItem) {
+                    if (n <= whole && n_gath <= kMaxGatherPerItem) {
                         items.push_back(make_item(sp, b, e, -1));
                         continue;
                     }

@@ -483,7 +483,7 @@ def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
     torch = torch_mod
     if case == "split_rows":    # global block rows make a split 128-row group: main kernel + merge kernel
         spec = W.MaskSpec(flags=W.BIGBIRD, block=64, n_window_blocks=3, n_global_blocks=2, n_random_blocks=2, seed=9)
-        B, H, S, d = 1, 4, 2048, 128
+        B, H, S, d = 1, 4, 4096, 128
     else:
         spec = W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=100, stride=32, stride_phase=1)
         B, H, S, d = 2, 2, 1500, 64
