@@ -1,7 +1,7 @@
 """Latency sweep of the masked-MHA forward over the paper's grid (Sec. 5.1 / Sec. 5.2: BERT-Base
 head shape 12 x 64, fp16, sequence 128..4096, batch 1..16, the four masks of Table 2).
 
-    python -m paper_2506_06095_amd.sweep [--seqs 128,512,...] [--batches 1,8,16] [--steps 100]
+    python -m paper_2506_06095_amd.sweep [--seqs 128,512,...] [--batches 1,8,16] [--steps 100] [--graph]
 
 Prints one markdown table row per (mask, batch, seq): latency of the selected kernel, of both
 kernels when forced, and of PyTorch's dense scaled_dot_product_attention with the same boolean
@@ -17,10 +17,30 @@ import sys
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 
-def _time(fn, stream, torch, steps, warmup):
+def _time(fn, stream, torch, steps, warmup, graph=False):
     for _ in range(warmup):
         fn()
+    torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if graph:
+        # 20 calls captured once and replayed: the device's time per call, without the host's call rate
+        per_graph = 20
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(per_graph):
+                    fn()
+        torch.cuda.synchronize()
+        g.replay()
+        replays = max(1, steps // per_graph)
+        a.record(stream)
+        for _ in range(replays):
+            g.replay()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / (replays * per_graph) * 1e3
     a.record(stream)
     for _ in range(steps):
         fn()
@@ -39,6 +59,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-dense", action="store_true", help="skip the PyTorch dense baseline")
+    ap.add_argument("--graph", action="store_true",
+                    help="time replays of a HIP graph holding 20 calls (device time per call, no host call rate)")
     args = ap.parse_args()
 
     import torch
@@ -68,12 +90,12 @@ def main() -> int:
                         if label == "auto":
                             chosen = "row" if info["kernel"] == smha.SMHA_KERNEL_ROW else "block"
                             nnz = info["nnz"] * (B * H // (info["Bm"] * info["Hm"]))
-                        us[label] = _time(lambda: plan.forward(q, k, v, out=out), stream, torch, args.steps, args.warmup)
+                        us[label] = _time(lambda: plan.forward(q, k, v, out=out), stream, torch, args.steps, args.warmup, args.graph)
                 dense_us = float("nan")
                 if not args.no_dense:
                     m = torch.from_numpy(W.dense_mask(spec, B, H, S).astype(bool)).cuda()
                     dense_us = _time(lambda: torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=m),
-                                     stream, torch, max(10, args.steps // 4), 3)
+                                     stream, torch, max(20, args.steps // 4), 3, args.graph)
                     del m
                 print(f"| {name} | {B} | {S} | {nnz / (B * H * S * S):.3f} | {chosen} | {us['auto']:.1f} | {us['block']:.1f} | "
                       f"{us['row']:.1f} | {dense_us:.1f} | {4.0 * nnz * d / us['auto'] / 1e6:.1f} |", flush=True)
