@@ -127,6 +127,9 @@ typedef struct {
  * The block kernel's own work lists (for inspection and tests; UNSUPPORTED if the plan has none):
  *   KERNEL_ITEMS int32[n_items of this mask][8]: {128-row group, first entry, end entry, scratch slot
  *     or -1, first gathered tile, gathered tiles, 0, 0}
+ *   KERNEL_ITEMS_FINE: the same groups cut to at most 16 entries per item; smha_forward walks these
+ *     instead when the call has too few items to fill the chip (few heads, long lists), so that the
+ *     longest list does not set the launch's duration
  *   KERNEL_ENTRIES int32[n][4], all masks: {key tile, code for the group's first 64 rows, code for its
  *     second 64 rows, gathered tile + 1 or 0}; code -2 = nothing, -1 = every entry set, >= 0 = block
  *     of KERNEL_BITMAPS.  An ordinary entry covers keys 64*tile .. 64*tile+63; a gathered one the 64
@@ -149,7 +152,8 @@ typedef enum {
     SMHA_EXPORT_KERNEL_ITEMS = 11,
     SMHA_EXPORT_KERNEL_ENTRIES = 12,
     SMHA_EXPORT_KERNEL_BITMAPS = 13,
-    SMHA_EXPORT_KERNEL_GATHER_KEYS = 14
+    SMHA_EXPORT_KERNEL_GATHER_KEYS = 14,
+    SMHA_EXPORT_KERNEL_ITEMS_FINE = 15
 } smha_export_t;
 
 /* Mask analysis (Sec. 4.2.1) from a dense boolean mask.

@@ -24,7 +24,7 @@ EXPORTS = {
     "full_row_ptr": (6, np.int32), "full_col_idx": (7, np.int32),
     "part_row_ptr": (8, np.int32), "part_col_idx": (9, np.int32),
     "bitmap_it8": (10, np.uint64),
-    "kernel_items": (11, np.int32), "kernel_entries": (12, np.int32),
+    "kernel_items": (11, np.int32), "kernel_items_fine": (15, np.int32), "kernel_entries": (12, np.int32),
     "kernel_bitmaps": (13, np.uint64), "kernel_gather_keys": (14, np.int32),
 }
 

@@ -1082,11 +1082,14 @@ smha_status_t upload_plan(smha_plan *p, int device_id) {
              to_device(d.col_off, p->h_col_off);
     }
     if (ok && p->has_block) {
-        ok = to_device(d.uent, p->h_uent) && to_device(d.gidx, p->h_gidx) && to_device(d.kt_bitmap, p->h_kt_bitmap) &&
-             to_device(d.items, p->h_items) &&
-             to_device(d.item_off, p->h_item_off) && to_device(d.item_cnt, p->h_item_cnt) &&
-             to_device(d.split_rows, p->h_split_rows) && to_device(d.split_off, p->h_split_off) &&
-             to_device(d.split_cnt, p->h_split_cnt);
+        ok = to_device(d.uent, p->h_uent) && to_device(d.gidx, p->h_gidx) && to_device(d.kt_bitmap, p->h_kt_bitmap);
+        for (int lvl = 0; ok && lvl < (p->fine_differs ? 2 : 1); ++lvl) {
+            const WorkLists &wl = p->lists[lvl];
+            ok = to_device(d.items[lvl], wl.items) &&
+                 to_device(d.item_off[lvl], wl.item_off) && to_device(d.item_cnt[lvl], wl.item_cnt) &&
+                 to_device(d.split_rows[lvl], wl.split_rows) && to_device(d.split_off[lvl], wl.split_off) &&
+                 to_device(d.split_cnt[lvl], wl.split_cnt);
+        }
     }
     (void)hipSetDevice(prev);
     if (!ok) {
@@ -1103,8 +1106,10 @@ void release_device(smha_plan *p) {
     (void)hipGetDevice(&prev);
     (void)hipSetDevice(p->device);
     DeviceArrays &d = p->dev;
-    void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap, d.items,
-                    d.item_off, d.item_cnt, d.split_rows, d.split_off, d.split_cnt, p->d_scratch};
+    void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap,
+                    d.items[0], d.item_off[0], d.item_cnt[0], d.split_rows[0], d.split_off[0], d.split_cnt[0],
+                    d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1],
+                    p->d_scratch};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
@@ -1124,10 +1129,10 @@ using namespace smha;
 static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0 && s[2] > 0); }
 
 template <int D, bool BF16, int OUT>
-static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
+static hipError_t launch_block_out(const smha_plan *plan, const WorkLists &wl, FwdParams &fp, hipStream_t stream) {
     const int BH = fp.B * fp.H;
     const int groups = (BH + 7) / 8;
-    fp.n_work = 8 * groups * plan->max_items;
+    fp.n_work = 8 * groups * wl.max_items;
     if (fp.n_work == 0) return hipSuccess;
     // two workgroups fit a CU (LDS at d = 128, registers at both head sizes)
     unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 4 : 2) * plan->n_cu);
@@ -1140,8 +1145,8 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
         hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false>), dim3(grid), dim3(256), 0, stream, fp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (plan->max_split_rows > 0) {
-        hipLaunchKernelGGL((smha_block_combine<D, OUT>), dim3(plan->max_split_rows, 8, BH), dim3(16 * (D / 4)), 0,
+    if (wl.max_split_rows > 0) {
+        hipLaunchKernelGGL((smha_block_combine<D, OUT>), dim3(wl.max_split_rows, 8, BH), dim3(16 * (D / 4)), 0,
                            stream, fp);
         e = hipGetLastError();
     }
@@ -1149,9 +1154,9 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
 }
 
 template <int D, bool BF16>
-static hipError_t launch_block(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
-    if (fp.out_dtype == SMHA_F32) return launch_block_out<D, BF16, SMHA_F32>(plan, fp, stream);
-    return launch_block_out<D, BF16, BF16 ? SMHA_BF16 : SMHA_F16>(plan, fp, stream);
+static hipError_t launch_block(const smha_plan *plan, const WorkLists &wl, FwdParams &fp, hipStream_t stream) {
+    if (fp.out_dtype == SMHA_F32) return launch_block_out<D, BF16, SMHA_F32>(plan, wl, fp, stream);
+    return launch_block_out<D, BF16, BF16 ? SMHA_BF16 : SMHA_F16>(plan, wl, fp, stream);
 }
 
 template <int D, bool BF16>
@@ -1219,10 +1224,24 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
-    fp.items = dv.items; fp.item_off = dv.item_off; fp.item_cnt = dv.item_cnt; fp.max_items = plan->max_items;
+    // Which grain of work items: the coarse lists unless they leave more than half of the chip's
+    // workgroup slots empty for this batch and head count (then the longest list would be the launch).
+    int lvl = 0;
+    if (plan->fine_differs) {
+        int64_t n_items = 0;
+        const WorkLists &w0 = plan->lists[0];
+        if (plan->Bm == 1 && plan->Hm == 1)
+            n_items = (int64_t)B * H * w0.item_cnt[0];
+        else
+            for (int bh = 0; bh < B * H; ++bh)
+                n_items += w0.item_cnt[(plan->Bm > 1 ? bh / H : 0) * plan->Hm + (plan->Hm > 1 ? bh % H : 0)];
+        if (2 * n_items < (int64_t)(d == 64 ? 4 : 2) * plan->n_cu) lvl = 1;
+    }
+    const WorkLists &wl = plan->lists[lvl];
+    fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl]; fp.max_items = wl.max_items;
     fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
-    fp.max_slots = plan->max_slots;
-    fp.split_rows = dv.split_rows; fp.split_off = dv.split_off; fp.split_cnt = dv.split_cnt;
+    fp.max_slots = wl.max_slots;
+    fp.split_rows = dv.split_rows[lvl]; fp.split_off = dv.split_off[lvl]; fp.split_cnt = dv.split_cnt[lvl];
     fp.row_ptr = dv.row_ptr; fp.col_idx = dv.col_idx; fp.col_off = dv.col_off;
 
 #ifdef SMHA_DEV
@@ -1232,8 +1251,8 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;
     if (which == SMHA_KERNEL_BLOCK) {
-        if (plan->max_slots > 0) {
-            const size_t need = (size_t)B * H * plan->max_slots * (size_t)(128 * d + 256) * sizeof(float);
+        if (wl.max_slots > 0) {
+            const size_t need = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 256) * sizeof(float);
             std::lock_guard<std::mutex> lock(plan->scratch_mutex);
             if (need > plan->scratch_bytes) {
                 if (plan->d_scratch) {
@@ -1256,9 +1275,9 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
             fp.scratch = plan->d_scratch;
         }
         if (d == 64)
-            e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, fp, stream) : launch_block<64, false>(plan, fp, stream);
+            e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, wl, fp, stream) : launch_block<64, false>(plan, wl, fp, stream);
         else
-            e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, fp, stream) : launch_block<128, false>(plan, fp, stream);
+            e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, wl, fp, stream) : launch_block<128, false>(plan, wl, fp, stream);
     } else {
         if (d == 64)
             e = in_dtype == SMHA_BF16 ? launch_row<64, true>(plan, fp, stream) : launch_row<64, false>(plan, fp, stream);

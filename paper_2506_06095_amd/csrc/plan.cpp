@@ -581,10 +581,14 @@ smha_status_t finish_plan(smha_plan *p) {
                 int64_t n_nonempty = 0;
                 for (int sp = 0; sp < nsup; ++sp) n_nonempty += sup_ptr[sp + 1] > sup_ptr[sp];
                 const double avg = n_nonempty ? (double)sup_ptr[nsup] / n_nonempty : 0.0;
-                const int chunk = std::min(64, std::max(16, (int)std::ceil(1.5 * avg)));  // the kernel holds one entry per lane
-                // lists up to twice that stay whole: merging costs a second launch (4-6 us), more than
-                // a workgroup that runs a few steps longer than the others
-                const int whole = std::min(64, 2 * chunk);
+                for (int lvl = 0; lvl < 2; ++lvl) {
+                // Grain 0: parts of at most `chunk` steps (the kernel holds one entry per lane: 64 at
+                // most), and lists up to twice that stay whole: merging costs a second launch (4-6 us),
+                // more than a workgroup that runs a few steps longer than the others.  Grain 1: at most
+                // 16 steps per item, for calls with so few heads that one long list would be the launch.
+                const int chunk = lvl == 0 ? std::min(64, std::max(16, (int)std::ceil(1.5 * avg))) : 16;
+                const int whole = lvl == 0 ? std::min(64, 2 * chunk) : 16;
+                WorkLists &wl = p->lists[lvl];
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
@@ -634,15 +638,16 @@ smha_status_t finish_plan(smha_plan *p) {
                 std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
                     return (a.end - a.begin) > (b.end - b.begin);
                 });
-                p->h_item_off.push_back((int32_t)p->h_items.size());
-                p->h_item_cnt.push_back((int32_t)items.size());
-                p->h_items.insert(p->h_items.end(), items.begin(), items.end());
-                p->h_split_off.push_back((int32_t)p->h_split_rows.size());
-                p->h_split_cnt.push_back((int32_t)splits.size());
-                p->h_split_rows.insert(p->h_split_rows.end(), splits.begin(), splits.end());
-                p->max_items = std::max(p->max_items, (int)items.size());
-                p->max_split_rows = std::max(p->max_split_rows, (int)splits.size());
-                p->max_slots = std::max(p->max_slots, (int)slots);
+                wl.item_off.push_back((int32_t)wl.items.size());
+                wl.item_cnt.push_back((int32_t)items.size());
+                wl.items.insert(wl.items.end(), items.begin(), items.end());
+                wl.split_off.push_back((int32_t)wl.split_rows.size());
+                wl.split_cnt.push_back((int32_t)splits.size());
+                wl.split_rows.insert(wl.split_rows.end(), splits.begin(), splits.end());
+                wl.max_items = std::max(wl.max_items, (int)items.size());
+                wl.max_split_rows = std::max(wl.max_split_rows, (int)splits.size());
+                wl.max_slots = std::max(wl.max_slots, (int)slots);
+                }
             }
         }
         // a gathered tile serves both tile rows of its group: it counts as two tiles
@@ -657,6 +662,8 @@ smha_status_t finish_plan(smha_plan *p) {
         p->kernel = choice;
         p->has_row = p->opts.build_both || choice == SMHA_KERNEL_ROW;
         p->has_block = p->opts.build_both || choice == SMHA_KERNEL_BLOCK;
+        p->fine_differs = p->lists[1].items.size() != p->lists[0].items.size();
+        if (!p->fine_differs) p->lists[1] = WorkLists{};  // (same cuts: one copy serves both)
         if (p->has_block) {
             p->h_kt_bitmap.insert(p->h_kt_bitmap.end(), 64, 0ull);  // spare all-zero block
             p->h_uent.push_back(UEntry{0, {-2, -2}, 0});             // spare entry: an empty item may read one past its list
@@ -664,10 +671,8 @@ smha_status_t finish_plan(smha_plan *p) {
             std::vector<UEntry>().swap(p->h_uent);
             std::vector<int32_t>().swap(p->h_gidx);
             std::vector<uint64_t>().swap(p->h_kt_bitmap);
-            std::vector<Item>().swap(p->h_items);
-            std::vector<SplitRow>().swap(p->h_split_rows);
-            p->h_item_off.clear(); p->h_item_cnt.clear(); p->h_split_off.clear(); p->h_split_cnt.clear();
-            p->max_items = p->max_split_rows = p->max_slots = 0;
+            p->lists[0] = WorkLists{};
+            p->lists[1] = WorkLists{};
             p->n_gathered = 0;
         }
         // ---- row path: concatenate -------------------------------------------------
@@ -843,8 +848,8 @@ extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *
         i.n_tiles64 += (int64_t)m.kt_col.size();
     }
     i.n_union = p->h_uent.empty() ? 0 : (int64_t)p->h_uent.size() - 1;  // (without the spare entry)
-    i.n_items = (int64_t)p->h_items.size();
-    i.n_split_rows = (int64_t)p->h_split_rows.size();
+    i.n_items = (int64_t)p->lists[0].items.size();
+    i.n_split_rows = (int64_t)p->lists[0].split_rows.size();
     i.eq1_threshold = p->eq1_threshold;
     i.model_row_us = p->model_row_us;
     i.model_block_us = p->model_block_us;
@@ -902,8 +907,14 @@ extern "C" smha_status_t smha_plan_export(const smha_plan_t *p, int mask_index, 
             src = p->h_kt_bitmap.data(); bytes = (p->h_kt_bitmap.size() - 64) * sizeof(uint64_t); break;  // (without the spare block)
         case SMHA_EXPORT_KERNEL_ITEMS:
             if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
-            src = p->h_items.data() + p->h_item_off[mask_index];
-            bytes = (size_t)p->h_item_cnt[mask_index] * sizeof(Item); break;
+            src = p->lists[0].items.data() + p->lists[0].item_off[mask_index];
+            bytes = (size_t)p->lists[0].item_cnt[mask_index] * sizeof(Item); break;
+        case SMHA_EXPORT_KERNEL_ITEMS_FINE: {
+            if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+            const WorkLists &wl = p->lists[p->fine_differs ? 1 : 0];
+            src = wl.items.data() + wl.item_off[mask_index];
+            bytes = (size_t)wl.item_cnt[mask_index] * sizeof(Item); break;
+        }
         default: return SMHA_ERR_INVALID_ARG;
     }
     *need = bytes;

@@ -69,10 +69,21 @@ struct DeviceArrays {
     UEntry *uent = nullptr;
     int32_t *gidx = nullptr;                               // [n gathered tiles][64] key numbers
     uint64_t *kt_bitmap = nullptr;
-    Item *items = nullptr;
-    int32_t *item_off = nullptr, *item_cnt = nullptr;      // [n_masks]
-    SplitRow *split_rows = nullptr;
-    int32_t *split_off = nullptr, *split_cnt = nullptr;    // [n_masks]
+    // work items at two grains (WorkLists below); [1] stays null when it would equal [0]
+    Item *items[2] = {nullptr, nullptr};
+    int32_t *item_off[2] = {nullptr, nullptr}, *item_cnt[2] = {nullptr, nullptr};      // [n_masks]
+    SplitRow *split_rows[2] = {nullptr, nullptr};
+    int32_t *split_off[2] = {nullptr, nullptr}, *split_cnt[2] = {nullptr, nullptr};    // [n_masks]
+};
+
+// The block kernel's work items for every mask of a plan: each 128-row group's list of steps, whole
+// or cut into parts whose partial results the merge kernel combines.
+struct WorkLists {
+    std::vector<Item> items;
+    std::vector<int32_t> item_off, item_cnt;
+    std::vector<SplitRow> split_rows;
+    std::vector<int32_t> split_off, split_cnt;
+    int max_items = 0, max_split_rows = 0, max_slots = 0;
 };
 
 }  // namespace smha
@@ -92,11 +103,11 @@ struct smha_plan {
     std::vector<smha::UEntry> h_uent;
     std::vector<int32_t> h_gidx;  // gathered tiles: 64 key numbers each
     std::vector<uint64_t> h_kt_bitmap;
-    std::vector<smha::Item> h_items;
-    std::vector<int32_t> h_item_off, h_item_cnt;
-    std::vector<smha::SplitRow> h_split_rows;
-    std::vector<int32_t> h_split_off, h_split_cnt;
-    int max_items = 0, max_split_rows = 0, max_slots = 0;
+    // [0]: lists cut only where they are much longer than the typical one (throughput: many heads
+    // keep the chip busy); [1]: every list cut to at most 16 steps (latency: with few heads the
+    // longest list is the whole launch).  smha_forward picks by how many items the call has.
+    smha::WorkLists lists[2];
+    bool fine_differs = false;  // false: [1] is empty and [0] serves both
     int64_t n_gathered = 0;
 
     int device = -1;  // -1: nothing uploaded

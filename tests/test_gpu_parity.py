@@ -336,6 +336,29 @@ def test_split_rows_merge_matches_unsplit_semantics(torch_mod, smha):
         run_case(torch_mod, smha, Q, K, V, "f16", masks, 0, plan=plan, what="split")
 
 
+@pytest.mark.parametrize("d,dtype", [(64, "f16"), (128, "bf16")])
+def test_few_heads_take_the_fine_work_items_and_agree_with_many_heads(torch_mod, smha, d, dtype):
+    """One plan, one mask: a call with 2 heads leaves the chip mostly empty and walks the lists cut to 16
+    steps (partials merged), a call with 160 heads walks the whole lists; the heads they share must agree
+    with the oracle, and with each other to rounding."""
+    torch = torch_mod
+    S = 4096
+    spec = W.table2_spec("causal")
+    masks = W.dense_mask(spec, 1, 1, S)
+    Q, K, V = W.qkv_bits(1, 2, S, d, dtype, 1.0, 21)
+    with smha.Plan.from_desc(spec, 1, 2, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        coarse = plan.export("kernel_items").reshape(-1, 8)
+        fine = plan.export("kernel_items_fine").reshape(-1, 8)
+        assert len(fine) > len(coarse) and (coarse[:, 3] == -1).all() and (fine[:, 3] >= 0).any()
+        few = run_case(torch, smha, Q, K, V, dtype, masks, 0, plan=plan, out_f32=True, what="few heads")
+        q, k, v = (to_dev(torch, np.ascontiguousarray(np.tile(x, (1, 80, 1, 1))), dtype) for x in (Q, K, V))
+        many = plan.forward(q, k, v, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        many = many.cpu().numpy()
+        assert np.array_equal(many[:, :2], many[:, 158:160])           # replicated heads: identical results
+        assert np.abs(many[:, :2].astype(np.float64) - few).max() <= 1e-3
+
+
 def test_strided_tensors_device_mask_and_determinism(torch_mod, smha):
     torch = torch_mod
     c = W.config(2)

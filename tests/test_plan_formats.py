@@ -212,9 +212,9 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
-def mask_from_kernel_lists(plan, mi, Sq, Sk):
+def mask_from_kernel_lists(plan, mi, Sq, Sk, which="kernel_items", longest=64):
     """Rebuild mask `mi` from the block kernel's work lists, counting how often each entry is visited."""
-    items = plan.export("kernel_items", mi).reshape(-1, 8)
+    items = plan.export(which, mi).reshape(-1, 8)
     ents = plan.export("kernel_entries").reshape(-1, 4)
     bmp = plan.export("kernel_bitmaps").reshape(-1, 64)
     keys = plan.export("kernel_gather_keys").reshape(-1, 64)
@@ -222,7 +222,7 @@ def mask_from_kernel_lists(plan, mi, Sq, Sk):
     bit = np.arange(64, dtype=np.uint64)
     for qtile, begin, end, slot, gbegin, gcount, _, _ in items:
         gath = [e for e in range(begin, end) if ents[e, 3] > 0]
-        assert len(gath) == gcount <= 16 and end - begin <= 64
+        assert len(gath) == gcount <= 16 and end - begin <= longest
         assert gath == list(range(end - gcount, end))        # gathered tiles close an item's list
         for t, e in enumerate(gath):
             assert ents[e, 3] - 1 == gbegin + t
@@ -239,6 +239,31 @@ def mask_from_kernel_lists(plan, mi, Sq, Sk):
                     blk = ((bmp[code][:, None] >> bit[None, :]) & np.uint64(1)).astype(np.int32)
                 np.add.at(cnt, (np.arange(r0, r0 + 64)[:, None], np.minimum(kk, Sk + 191)[None, :]), blk)
     return cnt
+
+
+def test_fine_work_items_cut_every_list_to_16_steps_and_number_their_partials():
+    spec = W.table2_spec("causal")
+    with smha.Plan.from_desc(spec, 1, 1, 4096, head_dim=64, device_id=-2, force=smha.SMHA_KERNEL_BLOCK) as p:
+        coarse = p.export("kernel_items").reshape(-1, 8)
+        fine = p.export("kernel_items_fine").reshape(-1, 8)
+        assert len(coarse) == 32 and (coarse[:, 3] == -1).all()            # nothing split at the coarse grain
+        assert (fine[:, 2] - fine[:, 1]).max() == 16 and len(fine) > len(coarse)
+        for g in range(32):                                                # each group: its parts tile its list
+            whole = coarse[coarse[:, 0] == g][0]
+            parts = fine[fine[:, 0] == g]
+            parts = parts[np.argsort(parts[:, 1])]
+            assert parts[0, 1] == whole[1] and parts[-1, 2] == whole[2]
+            assert np.array_equal(parts[1:, 1], parts[:-1, 2])
+            if len(parts) == 1:
+                assert parts[0, 3] == -1
+            else:
+                assert np.array_equal(parts[:, 3], parts[0, 3] + np.arange(len(parts)))   # consecutive scratch slots
+        split = fine[fine[:, 3] >= 0][:, 3]
+        assert np.array_equal(np.sort(split), np.arange(len(split)))      # slots dense from 0
+    # a mask whose lists are short has one grain only: the fine export is the coarse one
+    with smha.Plan.from_desc(W.table2_spec("sliding_window"), 1, 1, 2048, head_dim=64, device_id=-2,
+                             force=smha.SMHA_KERNEL_BLOCK) as p:
+        assert np.array_equal(p.export("kernel_items"), p.export("kernel_items_fine"))
 
 
 @pytest.mark.parametrize("name", ["cfg3", "strided_cols", "scattered", "rect_scattered", "mixed_long_rows"])
@@ -268,8 +293,9 @@ def test_kernel_work_lists_with_gathered_tiles_cover_the_mask_exactly_once(name)
         assert ip["n_tiles64"] == iq["n_tiles64"]
         for plan in (p, q):
             for mi in range(Bm * Hm):
-                cnt = mask_from_kernel_lists(plan, mi, Sq, Sk)
-                assert np.array_equal(cnt[:Sq, :Sk], masks[mi // Hm, mi % Hm].astype(np.int32)), (name, mi)
-                assert cnt[Sq:].sum() == 0 and cnt[:, Sk:].sum() == 0
+                for which, longest in (("kernel_items", 64), ("kernel_items_fine", 16)):
+                    cnt = mask_from_kernel_lists(plan, mi, Sq, Sk, which, longest)
+                    assert np.array_equal(cnt[:Sq, :Sk], masks[mi // Hm, mi % Hm].astype(np.int32)), (name, mi, which)
+                    assert cnt[Sq:].sum() == 0 and cnt[:, Sk:].sum() == 0
         for k in ("load_row_ptr", "load_col_idx", "flags", "bitmap"):  # the exported formats do not change
             assert np.array_equal(p.export(k), q.export(k))
