@@ -205,10 +205,13 @@ smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_exp
  *                   each tensor must span less than 2 GiB (UNSUPPORTED otherwise).
  *   scale           <= 0 selects 1/sqrt(d)
  *   kernel          AUTO = the plan's choice; ROW/BLOCK need that format in the plan
- * The plan is read-only here except for a scratch buffer the block kernel uses when a
- * query tile is split along keys; it is grown (hipMalloc) on the first call that needs
- * more room, so two forwards on one plan must not overlap on different streams, and a
- * call that may grow it must not be captured into a HIP graph (warm up once first).
+ * The plan is read-only here except for two device buffers the block kernel uses: the
+ * work order (which workgroup takes which work item; made and uploaded on the first call
+ * and whenever B, H or d differ from the previous call's) and a scratch buffer for query
+ * tiles that are split along keys (grown on the first call that needs more room).  Both
+ * steps call hipMalloc, so two forwards on one plan must not overlap on different
+ * streams, and a call that may take either step must not be captured into a HIP graph
+ * (warm up once with the same B, H and d first).
  * Errors: INVALID_ARG, UNSUPPORTED (d, dtype, alignment, missing format), SHAPE, ALLOC, HIP. */
 smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K, const void *V,
                            void *O, int B, int H, int d, smha_dtype_t in_dtype,
@@ -216,6 +219,26 @@ smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K
                            const int64_t k_strides[3], const int64_t v_strides[3],
                            const int64_t o_strides[3], float scale, smha_kernel_t kernel,
                            void *hip_stream);
+
+/* The block kernel's work order for B x H heads when workgroups_per_xcd workgroups are
+ * resident on each of the chip's 8 XCDs (smha_forward uses 2 per compute unit at d = 128,
+ * 4 at d = 64): the plan's work items (the workgroup tiling of Algorithm 1's outer loop)
+ * differ in length, and each head's items go, longest first, to the workgroup with the
+ * least work so far.  For inspection and tests; runs on the host.
+ *   fine       0: the items of SMHA_EXPORT_KERNEL_ITEMS, 1: those of KERNEL_ITEMS_FINE
+ *   host_dst   host, int32: 8 list starts (in pairs), 8 list lengths (in pairs), then the
+ *              lists: (batch*head, index into that grain's items of all masks, masks in
+ *              order) pairs.  XCD x serves the heads with batch*head mod 8 = x; the
+ *              workgroup of rank r takes positions r, r + *per_xcd, ... of its XCD's list
+ *              until the list ends or a pair with batch*head = -1 (no more work for this
+ *              rank) comes up.
+ *   cap, need  capacity of host_dst and the size needed, in int32 words (call with cap 0
+ *              to learn the size); nothing is written if cap < *need
+ *   per_xcd    workgroups per XCD actually used (<= workgroups_per_xcd); may be NULL
+ * Errors: INVALID_ARG, SHAPE (B, H against the plan's masks), UNSUPPORTED (no block format). */
+smha_status_t smha_plan_work_order(const smha_plan_t *plan, int B, int H, int workgroups_per_xcd,
+                                   int fine, int32_t *host_dst, size_t cap, size_t *need,
+                                   int *per_xcd);
 
 void smha_plan_destroy(smha_plan_t *plan); /* NULL is allowed */
 

@@ -92,6 +92,9 @@ def _load():
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                  C.POINTER(C.c_int64), C.c_float, C.c_int, vp]
     lib.smha_forward.restype = C.c_int
+    lib.smha_plan_work_order.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
+                                         C.POINTER(C.c_size_t), C.POINTER(C.c_int)]
+    lib.smha_plan_work_order.restype = C.c_int
     lib.smha_plan_destroy.argtypes = [vp]
     lib.smha_plan_destroy.restype = None
     lib.smha_status_string.argtypes = [C.c_int]
@@ -195,6 +198,22 @@ def smha_plan_export(plan: int, which: str, mask_index: int = 0) -> np.ndarray:
     return out
 
 
+def smha_plan_work_order(plan: int, B: int, H: int, workgroups_per_xcd: int, fine: bool = False):
+    """(table, per_xcd): int32 table = 8 list starts, 8 list lengths, then (batch*head, item) pairs."""
+    lib = _load()
+    need, per = C.c_size_t(0), C.c_int(0)
+    st = lib.smha_plan_work_order(C.c_void_p(plan), B, H, workgroups_per_xcd, int(fine), None, 0, C.byref(need),
+                                  C.byref(per))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_work_order")
+    out = np.empty(need.value, dtype=np.int32)
+    st = lib.smha_plan_work_order(C.c_void_p(plan), B, H, workgroups_per_xcd, int(fine),
+                                  C.c_void_p(out.ctypes.data), need.value, C.byref(need), C.byref(per))
+    if st != 0:
+        raise SmhaError(st, "smha_plan_work_order")
+    return out, per.value
+
+
 def smha_plan_destroy(plan: Optional[int]) -> None:
     if plan:
         _load().smha_plan_destroy(C.c_void_p(plan))
@@ -280,6 +299,9 @@ class Plan:
 
     def export(self, which: str, mask_index: int = 0) -> np.ndarray:
         return smha_plan_export(self.handle, which, mask_index)
+
+    def work_order(self, B: int, H: int, workgroups_per_xcd: int, fine: bool = False):
+        return smha_plan_work_order(self.handle, B, H, workgroups_per_xcd, fine)
 
     def forward(self, Q, K, V, out=None, out_dtype=None, scale: float = 0.0,
                 kernel: int = SMHA_KERNEL_AUTO, stream=None):

@@ -15,6 +15,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <vector>
 
 #include "smha_internal.hpp"
 
@@ -41,8 +42,13 @@ struct FwdParams {
     // block path
     const Item *items;
     const int32_t *item_off, *item_cnt;
-    int max_items;
-    int n_work;  // 8 * ceil(B*H/8) * max_items work slots (some empty)
+    // work order of the block kernel: for each XCD x a list of (batch*head, item index) pairs of the
+    // heads with batch*head mod 8 = x; the workgroup of rank r on that XCD (of gridDim.x / 8) takes
+    // positions r, r + gridDim.x / 8, ... until the list ends or a pair with batch*head < 0 comes up.
+    // order_hdr = {start of each XCD's list (8), length (8)}
+    const int32_t *order, *order_hdr;
+    int n_work;  // 8 * the longest list (bounds the development stamps)
+    int per_xcd; // workgroups per XCD the order was made for (host side: the grid is 8 times this)
     const UEntry *uent;
     const int32_t *gidx;  // gathered tiles: 64 key numbers each
     int n_gidx;           // entries of gidx
@@ -183,9 +189,12 @@ __device__ __forceinline__ u32x2 lds_read_tr(const uint16_t *src) {
 // output stores before its value could be used).
 template <typename T>
 __device__ __forceinline__ T uniform_load(const T *ptr) {
-    static_assert(sizeof(T) == 4 || sizeof(T) == 16, "one or four dwords");
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8 || sizeof(T) == 16, "one, two or four dwords");
     if constexpr (sizeof(T) == 4) {
         typedef const uint32_t __attribute__((address_space(4))) *const_ptr;
+        return __builtin_bit_cast(T, *(const_ptr)(uintptr_t)ptr);
+    } else if constexpr (sizeof(T) == 8) {
+        typedef const u32x2 __attribute__((address_space(4))) *const_ptr;
         return __builtin_bit_cast(T, *(const_ptr)(uintptr_t)ptr);
     } else {
         typedef const u32x4 __attribute__((address_space(4))) *const_ptr;
@@ -260,22 +269,24 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         int valid, b, h, bh, qtile, begin, n, slot, col0, code0[2], gid0;  // col0, code0, gid0: the first entry
         int gbegin, gcount;
     };
-    auto fetch_work = [&](int wg) __attribute__((always_inline)) {
+    const int xcd = blockIdx.x & 7, per_xcd = gridDim.x >> 3;
+    const int list_at = uniform_load(p.order_hdr + xcd), list_len = uniform_load(p.order_hdr + 8 + xcd);
+    auto fetch_work = [&](int pos) __attribute__((always_inline)) {  // position in this XCD's list
         Work wk;
-        const int xcd = wg & 7, rest = wg >> 3;
-        const int grp = rest / p.max_items, it = rest - grp * p.max_items;
-        wk.bh = grp * 8 + xcd;
-        wk.b = wk.bh / p.H;
-        wk.h = wk.bh - wk.b * p.H;
-        wk.valid = wg < p.n_work && wk.bh < p.B * p.H;
+        wk.valid = pos < list_len;
+        wk.bh = wk.b = wk.h = 0;
         wk.qtile = wk.begin = wk.n = wk.col0 = wk.gid0 = wk.gbegin = wk.gcount = 0;
         wk.slot = -1;
         wk.code0[0] = wk.code0[1] = -2;
         if (wk.valid) {
-            const int mask = (p.Bm > 1 ? wk.b : 0) * p.Hm + (p.Hm > 1 ? wk.h : 0);
-            wk.valid = it < uniform_load(p.item_cnt + mask);
+            struct Pair { int32_t bh, index; };
+            const Pair pr = uniform_load(reinterpret_cast<const Pair *>(p.order) + list_at + pos);
+            wk.valid = pr.bh >= 0;
+            wk.bh = max(pr.bh, 0);
+            wk.b = wk.bh / p.H;
+            wk.h = wk.bh - wk.b * p.H;
             if (wk.valid) {
-                const Item *ip = p.items + uniform_load(p.item_off + mask) + it;
+                const Item *ip = p.items + pr.index;
                 struct ItemHead { int32_t qtile, begin, end, slot; };
                 const ItemHead item = uniform_load(reinterpret_cast<const ItemHead *>(ip));
                 if constexpr (GATHER) {
@@ -381,22 +392,21 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     };
     // Invariant at the top of the loop: everything requested for the item has landed (each way
     // into the loop ends with the wait that makes it so, which lets the compiler see it too).
-    Work item = fetch_work(blockIdx.x);
+    int pos = blockIdx.x >> 3;
+    Work item = fetch_work(pos);
     if (item.valid) start_work(item);
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
-    for (int wg = blockIdx.x; wg < p.n_work; wg += gridDim.x) {
+    while (item.valid) {
+#ifdef SMHA_DEV
+    const int wg = xcd + 8 * pos;
+#endif
     STAMP(0);
 #ifdef SMHA_DEV
     unsigned long long ph[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = 0;
 #endif
     // the next item's descriptor: scalar loads that complete under this item's tiles
-    const Work nxt = fetch_work(wg + gridDim.x);
-    if (!item.valid) {  // (a hole in the work list: nothing was requested for it)
-        if (nxt.valid) start_work(nxt);
-        __builtin_amdgcn_s_waitcnt(0x0070);
-        item = nxt;
-        continue;
-    }
+    pos += per_xcd;
+    const Work nxt = fetch_work(pos);
     const int n = item.n;
     const int b = item.b, h = item.h, bh = item.bh;
     int e_col, e_code, e_gid = 0;
@@ -1109,12 +1119,14 @@ void release_device(smha_plan *p) {
     void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap,
                     d.items[0], d.item_off[0], d.item_cnt[0], d.split_rows[0], d.split_off[0], d.split_cnt[0],
                     d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1],
-                    p->d_scratch};
+                    p->d_scratch, p->d_order};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
     p->d_scratch = nullptr;
     p->scratch_bytes = 0;
+    p->d_order = nullptr;
+    p->order_B = p->order_H = p->order_slots = 0;
     p->device = -1;
     (void)hipSetDevice(prev);
 }
@@ -1131,14 +1143,10 @@ static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] %
 template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, const WorkLists &wl, FwdParams &fp, hipStream_t stream) {
     const int BH = fp.B * fp.H;
-    const int groups = (BH + 7) / 8;
-    fp.n_work = 8 * groups * wl.max_items;
     if (fp.n_work == 0) return hipSuccess;
-    // two workgroups fit a CU (LDS at d = 128, registers at both head sizes)
-    unsigned grid = (unsigned)std::min(fp.n_work, (D == 64 ? 4 : 2) * plan->n_cu);
-#ifdef SMHA_DEV
-    if (const char *g = getenv("SMHA_GRID")) grid = (unsigned)atoi(g);
-#endif
+    // the grid fills the chip once (two workgroups fit a CU at d = 128, four at d = 64: LDS and
+    // registers); the work order was made for exactly this many workgroups
+    const unsigned grid = 8u * (unsigned)fp.per_xcd;
     if (plan->n_gathered > 0)
         hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true>), dim3(grid), dim3(256), 0, stream, fp);
     else
@@ -1238,7 +1246,7 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
         if (2 * n_items < (int64_t)(d == 64 ? 4 : 2) * plan->n_cu) lvl = 1;
     }
     const WorkLists &wl = plan->lists[lvl];
-    fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl]; fp.max_items = wl.max_items;
+    fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl];
     fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
     fp.max_slots = wl.max_slots;
     fp.split_rows = dv.split_rows[lvl]; fp.split_off = dv.split_off[lvl]; fp.split_cnt = dv.split_cnt[lvl];
@@ -1251,6 +1259,47 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;
     if (which == SMHA_KERNEL_BLOCK) {
+        {   // the work order for this batch, head count and grid (kept until another one is asked for)
+            const int slots = (d == 64 ? 4 : 2) * plan->n_cu / 8;  // workgroups that fit an XCD at once
+            std::lock_guard<std::mutex> lock(plan->scratch_mutex);
+            if (plan->order_B != B || plan->order_H != H || plan->order_slots != slots || plan->order_lvl != lvl) {
+                std::vector<int32_t> table;
+                int per_xcd = 0;
+                build_work_order(plan, lvl, B, H, slots, table, per_xcd);
+                if (plan->d_order) {
+                    // earlier launches may still be reading the old table
+                    if (hipDeviceSynchronize() != hipSuccess || hipFree(plan->d_order) != hipSuccess) {
+                        (void)hipGetLastError();
+                        return SMHA_ERR_HIP;
+                    }
+                    plan->d_order = nullptr;
+                    plan->order_B = plan->order_H = plan->order_slots = 0;
+                }
+                void *ptr = nullptr;
+                if (hipMalloc(&ptr, table.size() * sizeof(int32_t)) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return SMHA_ERR_ALLOC;
+                }
+                if (hipMemcpy(ptr, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
+                    (void)hipGetLastError();
+                    (void)hipFree(ptr);
+                    return SMHA_ERR_HIP;
+                }
+                plan->d_order = (int32_t *)ptr;
+                plan->order_B = B;
+                plan->order_H = H;
+                plan->order_slots = slots;
+                plan->order_lvl = lvl;
+                plan->order_per_xcd = per_xcd;
+                int longest = 0;
+                for (int x = 0; x < 8; ++x) longest = std::max(longest, table[8 + x]);
+                plan->order_longest = longest;
+            }
+            fp.order_hdr = plan->d_order;
+            fp.order = plan->d_order + 16;
+            fp.n_work = 8 * plan->order_longest;
+            fp.per_xcd = plan->order_per_xcd;
+        }
         if (wl.max_slots > 0) {
             const size_t need = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 256) * sizeof(float);
             std::lock_guard<std::mutex> lock(plan->scratch_mutex);

@@ -5,9 +5,13 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <functional>
 #include <memory>
 #include <new>
+#include <queue>
 #include <thread>
+#include <utility>
+#include <vector>
 
 #include "smha_internal.hpp"
 
@@ -708,6 +712,61 @@ smha_status_t finish_plan(smha_plan *p) {
     return upload_plan(p, dev);
 }
 
+// The block kernel's work order for B x H heads on `slots` resident workgroups per XCD.  Items
+// differ in length (tile rows under global tokens, random blocks, padding), and with equal item
+// counts per workgroup the slowest one ends well after the average one; so the items of each head
+// go, longest first, to the workgroup with the least work so far (cost: tiles plus a fixed part per
+// item), head after head so that an XCD's workgroups stay on one head's K/V at a time.
+// table = {start of each XCD's list (8), its length (8), then (batch*head, item index) pairs};
+// list position = turn * per_xcd + workgroup rank; a workgroup's unused turns hold batch*head = -1.
+void build_work_order(const smha_plan *plan, int lvl, int B, int H, int slots, std::vector<int32_t> &table, int &per_xcd) {
+    const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
+    const int BH = B * H;
+    auto mask_of = [&](int bh) { return (plan->Bm > 1 ? bh / H : 0) * plan->Hm + (plan->Hm > 1 ? bh % H : 0); };
+    int64_t most = 0;  // items of the busiest XCD
+    for (int x = 0; x < 8; ++x) {
+        int64_t n = 0;
+        for (int bh = x; bh < BH; bh += 8) n += wl.item_cnt[mask_of(bh)];
+        most = std::max(most, n);
+    }
+    per_xcd = (int)std::min<int64_t>(slots, most);
+    table.assign(16, 0);
+    if (per_xcd == 0) return;
+    constexpr int kItemCost = 2;  // an item's start and end, in tiles
+    typedef std::pair<int64_t, int> Load;  // (work so far, workgroup rank)
+    std::vector<std::vector<int32_t>> mine(per_xcd);
+    for (int x = 0; x < 8; ++x) {
+        std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+        for (int r = 0; r < per_xcd; ++r) {
+            heap.push({0, r});
+            mine[r].clear();
+        }
+        for (int bh = x; bh < BH; bh += 8) {
+            const int mask = mask_of(bh);
+            const int32_t off = wl.item_off[mask];
+            for (int it = 0; it < wl.item_cnt[mask]; ++it) {  // (sorted by length, longest first)
+                const Item &item = wl.items[off + it];
+                Load l = heap.top();
+                heap.pop();
+                mine[l.second].push_back(bh);
+                mine[l.second].push_back(off + it);
+                l.first += kItemCost + (item.end - item.begin);
+                heap.push(l);
+            }
+        }
+        size_t turns = 0;
+        for (int r = 0; r < per_xcd; ++r) turns = std::max(turns, mine[r].size() / 2);
+        table[x] = (int32_t)((table.size() - 16) / 2);
+        table[8 + x] = (int32_t)(turns * per_xcd);
+        for (size_t t = 0; t < turns; ++t)
+            for (int r = 0; r < per_xcd; ++r) {
+                const bool has = 2 * t < mine[r].size();
+                table.push_back(has ? mine[r][2 * t] : -1);
+                table.push_back(has ? mine[r][2 * t + 1] : 0);
+            }
+    }
+}
+
 }  // namespace smha
 
 using namespace smha;
@@ -831,6 +890,22 @@ extern "C" smha_status_t smha_plan_from_desc(const smha_mask_desc_t *desc, int B
     } catch (const std::bad_alloc &) {
         return SMHA_ERR_ALLOC;
     }
+}
+
+extern "C" smha_status_t smha_plan_work_order(const smha_plan_t *p, int B, int H, int workgroups_per_xcd, int fine,
+                                              int32_t *host_dst, size_t cap, size_t *need, int *per_xcd) {
+    if (!p || !need || B < 1 || H < 1 || workgroups_per_xcd < 1 || fine < 0 || fine > 1) return SMHA_ERR_INVALID_ARG;
+    if (cap > 0 && !host_dst) return SMHA_ERR_INVALID_ARG;
+    if ((p->Bm != 1 && p->Bm != B) || (p->Hm != 1 && p->Hm != H)) return SMHA_ERR_SHAPE;
+    if (!p->has_block) return SMHA_ERR_UNSUPPORTED;
+    if ((int64_t)B * H > (1 << 24)) return SMHA_ERR_UNSUPPORTED;
+    std::vector<int32_t> table;
+    int n = 0;
+    try { build_work_order(p, fine, B, H, workgroups_per_xcd, table, n); } catch (const std::bad_alloc &) { return SMHA_ERR_ALLOC; }
+    *need = table.size();
+    if (per_xcd) *per_xcd = n;
+    if (cap >= table.size()) std::memcpy(host_dst, table.data(), table.size() * sizeof(int32_t));
+    return SMHA_OK;
 }
 
 extern "C" smha_status_t smha_plan_info(const smha_plan_t *p, smha_plan_info_t *out) {

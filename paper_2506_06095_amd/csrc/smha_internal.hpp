@@ -118,12 +118,18 @@ struct smha_plan {
     mutable std::mutex scratch_mutex;
     mutable float *d_scratch = nullptr;
     mutable size_t scratch_bytes = 0;
+    // the block kernel's work order for the last batch, head count and grid seen (same mutex): 16
+    // header words (start and length of each XCD's list), then (batch*head, item index) pairs
+    mutable int32_t *d_order = nullptr;
+    mutable int order_B = 0, order_H = 0, order_slots = 0, order_lvl = 0, order_per_xcd = 0, order_longest = 0;
 };
 
 namespace smha {
 
 // plan.cpp
 smha_status_t finish_plan(smha_plan *p);      // selector, work lists, concatenation
+// which workgroup of the block kernel takes which item, for B x H heads on `slots` workgroups per XCD
+void build_work_order(const smha_plan *plan, int lvl, int B, int H, int slots, std::vector<int32_t> &table, int &per_xcd);
 // device.hip
 smha_status_t upload_plan(smha_plan *p, int device_id);
 void release_device(smha_plan *p);

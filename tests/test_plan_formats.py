@@ -212,6 +212,70 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), n
 
 
+def check_work_order(plan, B, H, slots, fine=False):
+    """Every (batch*head, item) once, on the XCD of its head, ranks compact, loads balanced."""
+    info = plan.info()
+    Bm, Hm = info["Bm"], info["Hm"]
+    lengths, off = [], [0]
+    for m in range(Bm * Hm):
+        it = plan.export("kernel_items_fine" if fine else "kernel_items", m).reshape(-1, 8)
+        lengths.append(it[:, 2] - it[:, 1])
+        off.append(off[-1] + len(it))
+    all_len = np.concatenate(lengths)
+    table, per = plan.work_order(B, H, slots, fine)
+    assert 0 < per <= slots
+    pairs = table[16:].reshape(-1, 2)
+    seen = set()
+    ratio = 0.0
+    for x in range(8):
+        at, n = int(table[x]), int(table[8 + x])
+        assert n % per == 0
+        lst = pairs[at:at + n].reshape(-1, per, 2)          # [turn][rank]
+        loads = np.zeros(per, np.int64)
+        for r in range(per):
+            live = lst[:, r, 0] >= 0
+            assert not np.any(live[1:] & ~live[:-1])           # a rank's unused turns are its last ones
+            for bh, idx in lst[live, r]:
+                assert bh % 8 == x and 0 <= bh < B * H
+                mask = (bh // H if Bm > 1 else 0) * Hm + (bh % H if Hm > 1 else 0)
+                assert off[mask] <= idx < off[mask + 1]
+                assert (bh, idx) not in seen
+                seen.add((int(bh), int(idx)))
+                loads[r] += 2 + all_len[idx]
+            heads = lst[live, r, 0]
+            assert np.all(np.diff(heads) >= 0)                 # head after head
+        # greedy longest-first: no workgroup exceeds its XCD's mean by more than the longest item
+        assert loads.max() <= loads.mean() + 2 + int(all_len.max())
+        if loads.sum():
+            ratio = max(ratio, float(loads.max() / loads.mean()))
+    want = {(bh, i) for bh in range(B * H)
+            for i in range(off[(bh // H if Bm > 1 else 0) * Hm + (bh % H if Hm > 1 else 0)],
+                           off[(bh // H if Bm > 1 else 0) * Hm + (bh % H if Hm > 1 else 0) + 1])}
+    assert seen == want
+    return ratio
+
+
+def test_work_order_covers_every_item_once_and_balances():
+    c = W.config(2)
+    with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=64, head_dim=c.d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        check_work_order(plan, c.B, c.H, 128)
+        check_work_order(plan, c.B, c.H, 128, fine=True)
+        check_work_order(plan, c.B, c.H, 3)      # many turns per workgroup
+        check_work_order(plan, 1, 1, 64)         # fewer items than workgroups, seven idle XCDs
+    # per-head masks of unequal weight, a head count that is no multiple of 8
+    spec = W.MaskSpec(flags=W.WINDOW | W.GLOBAL | W.BLOCK_RANDOM | W.PADDING, window_left=64, window_right=64,
+                      n_global=70, keep_p=0.2, seed=5, per_head=True, valid_len=(2048, 1500))
+    with smha.Plan.from_desc(spec, 2, 5, 2048, block=64, head_dim=64, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        check_work_order(plan, 2, 5, 16)
+        check_work_order(plan, 2, 5, 16, fine=True)
+        assert check_work_order(plan, 2, 5, 3) <= 1.2
+    with smha.Plan.from_dense(np.zeros((1, 1, 256, 256), np.uint8), force=smha.SMHA_KERNEL_BLOCK) as plan:
+        check_work_order(plan, 4, 4, 64)         # empty lists only (the items still write zeros)
+    with smha.Plan.from_dense(np.ones((2, 3, 64, 64), np.uint8), force=smha.SMHA_KERNEL_BLOCK) as plan:
+        with pytest.raises(smha.SmhaError):
+            plan.work_order(3, 3, 64)            # batch does not match the plan's masks
+
+
 def mask_from_kernel_lists(plan, mi, Sq, Sk, which="kernel_items", longest=64):
     """Rebuild mask `mi` from the block kernel's work lists, counting how often each entry is visited."""
     items = plan.export(which, mi).reshape(-1, 8)
