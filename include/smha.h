@@ -206,13 +206,14 @@ smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_exp
  *   scale           <= 0 selects 1/sqrt(d)
  *   kernel          AUTO = the plan's choice; ROW/BLOCK need that format in the plan
  * The plan is read-only here except for two device buffers the block kernel uses: the
- * work order (which workgroup takes which work item; made and uploaded on the first call
- * and whenever B, H or d differ from the previous call's) and a scratch buffer for query
+ * work order (which workgroup takes which work item; made and uploaded at the first call
+ * with a given B, H and d; the eight most recent combinations are kept) and a scratch buffer for query
  * tiles that are split along keys (grown on the first call that needs more room).  Both
  * steps call hipMalloc, so two forwards on one plan must not overlap on different
  * streams, and a call that may take either step must not be captured into a HIP graph
  * (warm up once with the same B, H and d first).
- * Errors: INVALID_ARG, UNSUPPORTED (d, dtype, alignment, missing format), SHAPE, ALLOC, HIP. */
+ * Errors: INVALID_ARG, UNSUPPORTED (d, dtype, alignment, missing format, more than 2^28
+ * work items in one call), SHAPE, ALLOC, HIP. */
 smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K, const void *V,
                            void *O, int B, int H, int d, smha_dtype_t in_dtype,
                            smha_dtype_t out_dtype, const int64_t q_strides[3],

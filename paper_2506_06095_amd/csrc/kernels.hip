@@ -1119,14 +1119,16 @@ void release_device(smha_plan *p) {
     void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap,
                     d.items[0], d.item_off[0], d.item_cnt[0], d.split_rows[0], d.split_off[0], d.split_cnt[0],
                     d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1],
-                    p->d_scratch, p->d_order};
+                    p->d_scratch,
+                    p->orders[0].dev, p->orders[1].dev, p->orders[2].dev, p->orders[3].dev,
+                    p->orders[4].dev, p->orders[5].dev, p->orders[6].dev, p->orders[7].dev};
+    static_assert(smha_plan::kOrders == 8, "the list above names every cached work order");
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
     p->d_scratch = nullptr;
     p->scratch_bytes = 0;
-    p->d_order = nullptr;
-    p->order_B = p->order_H = p->order_slots = 0;
+    for (smha_plan::Order &o : p->orders) o = smha_plan::Order{};
     p->device = -1;
     (void)hipSetDevice(prev);
 }
@@ -1259,21 +1261,26 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;
     if (which == SMHA_KERNEL_BLOCK) {
-        {   // the work order for this batch, head count and grid (kept until another one is asked for)
+        if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
+        {   // the work order for this batch, head count, grid and grain (the eight most recent are kept)
             const int slots = (d == 64 ? 4 : 2) * plan->n_cu / 8;  // workgroups that fit an XCD at once
             std::lock_guard<std::mutex> lock(plan->scratch_mutex);
-            if (plan->order_B != B || plan->order_H != H || plan->order_slots != slots || plan->order_lvl != lvl) {
+            smha_plan::Order *hit = nullptr, *victim = &plan->orders[0];
+            for (smha_plan::Order &o : plan->orders) {
+                if (o.dev && o.B == B && o.H == H && o.slots == slots && o.lvl == lvl) hit = &o;
+                if (!o.dev || (victim->dev && o.last_use < victim->last_use)) victim = &o;
+            }
+            if (!hit) {
                 std::vector<int32_t> table;
                 int per_xcd = 0;
                 build_work_order(plan, lvl, B, H, slots, table, per_xcd);
-                if (plan->d_order) {
-                    // earlier launches may still be reading the old table
-                    if (hipDeviceSynchronize() != hipSuccess || hipFree(plan->d_order) != hipSuccess) {
+                if (victim->dev) {
+                    // earlier launches may still be reading the table that makes room
+                    if (hipDeviceSynchronize() != hipSuccess || hipFree(victim->dev) != hipSuccess) {
                         (void)hipGetLastError();
                         return SMHA_ERR_HIP;
                     }
-                    plan->d_order = nullptr;
-                    plan->order_B = plan->order_H = plan->order_slots = 0;
+                    *victim = smha_plan::Order{};
                 }
                 void *ptr = nullptr;
                 if (hipMalloc(&ptr, table.size() * sizeof(int32_t)) != hipSuccess) {
@@ -1285,20 +1292,21 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
                     (void)hipFree(ptr);
                     return SMHA_ERR_HIP;
                 }
-                plan->d_order = (int32_t *)ptr;
-                plan->order_B = B;
-                plan->order_H = H;
-                plan->order_slots = slots;
-                plan->order_lvl = lvl;
-                plan->order_per_xcd = per_xcd;
-                int longest = 0;
-                for (int x = 0; x < 8; ++x) longest = std::max(longest, table[8 + x]);
-                plan->order_longest = longest;
+                hit = victim;
+                hit->dev = (int32_t *)ptr;
+                hit->B = B;
+                hit->H = H;
+                hit->slots = slots;
+                hit->lvl = lvl;
+                hit->per_xcd = per_xcd;
+                hit->longest = 0;
+                for (int x = 0; x < 8; ++x) hit->longest = std::max(hit->longest, table[8 + x]);
             }
-            fp.order_hdr = plan->d_order;
-            fp.order = plan->d_order + 16;
-            fp.n_work = 8 * plan->order_longest;
-            fp.per_xcd = plan->order_per_xcd;
+            hit->last_use = ++plan->order_clock;
+            fp.order_hdr = hit->dev;
+            fp.order = hit->dev + 16;
+            fp.n_work = 8 * hit->longest;
+            fp.per_xcd = hit->per_xcd;
         }
         if (wl.max_slots > 0) {
             const size_t need = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 256) * sizeof(float);

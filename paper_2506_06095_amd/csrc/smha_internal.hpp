@@ -118,10 +118,17 @@ struct smha_plan {
     mutable std::mutex scratch_mutex;
     mutable float *d_scratch = nullptr;
     mutable size_t scratch_bytes = 0;
-    // the block kernel's work order for the last batch, head count and grid seen (same mutex): 16
-    // header words (start and length of each XCD's list), then (batch*head, item index) pairs
-    mutable int32_t *d_order = nullptr;
-    mutable int order_B = 0, order_H = 0, order_slots = 0, order_lvl = 0, order_per_xcd = 0, order_longest = 0;
+    // The block kernel's work orders (same mutex), one per (batch, heads, workgroups per XCD, grain)
+    // seen, the eight most recent kept: 16 header words (start and length of each XCD's list), then
+    // (batch*head, item index) pairs.
+    struct Order {
+        int B = 0, H = 0, slots = 0, lvl = 0, per_xcd = 0, longest = 0;
+        int32_t *dev = nullptr;
+        uint64_t last_use = 0;
+    };
+    static constexpr int kOrders = 8;
+    mutable Order orders[kOrders];
+    mutable uint64_t order_clock = 0;
 };
 
 namespace smha {

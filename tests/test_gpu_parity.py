@@ -359,6 +359,26 @@ def test_few_heads_take_the_fine_work_items_and_agree_with_many_heads(torch_mod,
         assert np.abs(many[:, :2].astype(np.float64) - few).max() <= 1e-3
 
 
+def test_one_plan_serves_many_batch_sizes_in_turn(torch_mod, smha):
+    """The plan keeps a work order per (batch, heads) it has seen, a few at a time: going round more batch
+    sizes than it keeps, twice, every call must still give each replicated head the same rows."""
+    torch = torch_mod
+    S, d, H = 700, 64, 3
+    spec = W.MaskSpec(flags=W.WINDOW | W.GLOBAL, window_left=50, window_right=10, n_global=5)
+    masks = W.dense_mask(spec, 1, 1, S)
+    Q, K, V = W.qkv_bits(1, H, S, d, "f16", 1.0, 33)
+    ref = oracle.masked_attention(Q, K, V, "f16", masks)
+    with smha.Plan.from_desc(spec, 1, H, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        for rnd in range(2):
+            for B in (1, 2, 3, 5, 7, 11, 13, 4, 6, 9, 12):
+                q, k, v = (to_dev(torch, np.ascontiguousarray(np.tile(x, (B, 1, 1, 1))), "f16") for x in (Q, K, V))
+                out = plan.forward(q, k, v, out_dtype=torch.float32)
+                torch.cuda.synchronize()
+                got = out.cpu().numpy()
+                assert all(np.array_equal(got[b], got[0]) for b in range(1, B)), (rnd, B)
+                check(got[:1], ref, f"round {rnd} batch {B}")
+
+
 def test_strided_tensors_device_mask_and_determinism(torch_mod, smha):
     torch = torch_mod
     c = W.config(2)
