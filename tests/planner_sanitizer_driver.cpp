@@ -18,13 +18,26 @@ smha_status_t classify_device_mask(const uint8_t *, int, int, int, std::vector<T
 static uint64_t rng_state = 12345;
 static uint32_t rnd() { rng_state = rng_state * 6364136223846793005ull + 1442695040888963407ull; return (uint32_t)(rng_state >> 33); }
 static void exports(smha_plan_t *p, int n_masks) {
-    for (int which = 0; which <= 14; ++which)
+    for (int which = 0; which <= 15; ++which)
         for (int mi = 0; mi < n_masks; ++mi) {
             size_t need = 0;
             if (smha_plan_export(p, mi, (smha_export_t)which, nullptr, 0, &need) != SMHA_OK) continue;
             std::vector<char> buf(need + 1);
             smha_plan_export(p, mi, (smha_export_t)which, buf.data(), need, &need);
         }
+    // the work order, both grains, for a few batch and head counts the plan's masks allow
+    smha_plan_info_t info;
+    if (smha_plan_info(p, &info) != SMHA_OK) return;
+    for (int fine = 0; fine < 2; ++fine)
+        for (int B : {info.Bm, info.Bm == 1 ? 3 : info.Bm})
+            for (int H : {info.Hm, info.Hm == 1 ? 9 : info.Hm})
+                for (int slots : {1, 7, 128}) {
+                    size_t need = 0;
+                    int per = 0;
+                    if (smha_plan_work_order(p, B, H, slots, fine, nullptr, 0, &need, &per) != SMHA_OK) continue;
+                    std::vector<int32_t> buf(need);
+                    smha_plan_work_order(p, B, H, slots, fine, buf.data(), need, &need, &per);
+                }
 }
 int main() {
     int n = 0;
