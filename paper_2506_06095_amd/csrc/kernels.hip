@@ -342,11 +342,15 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(p.Sk - 1) * p.ks.s + D) * 2);
         rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(p.Sk - 1) * p.vs.s + D) * 2);
         {
+            // (one 16-byte request per lane: every memory instruction here holds the wave ~100 cycles)
+            typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+            static_assert(sizeof(UEntry) == 16, "an entry is loaded as one vector");
             const UEntry *u = p.uent + wk.begin + min(lane, max(wk.n - 1, 0));
-            raw_col = __builtin_nontemporal_load(&u->col);
-            raw_code0 = __builtin_nontemporal_load(&u->code[0]);
-            raw_code1 = __builtin_nontemporal_load(&u->code[1]);
-            if constexpr (GATHER) raw_gid = __builtin_nontemporal_load(&u->gather);
+            const i32x4 ev = __builtin_nontemporal_load(reinterpret_cast<const i32x4 *>(u));
+            raw_col = ev[0];
+            raw_code0 = ev[1];
+            raw_code1 = ev[2];
+            if constexpr (GATHER) raw_gid = ev[3];
             const int c0 = (w >> 1) ? wk.code0[1] : wk.code0[0];
             raw_word = 0;
             if (c0 >= 0) raw_word = p.kt_bitmap[(size_t)c0 * 64 + 32 * (w & 1) + j];
