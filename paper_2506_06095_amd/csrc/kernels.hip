@@ -105,17 +105,15 @@ __device__ __forceinline__ float widen16(uint32_t bits16) {
 
 __device__ __forceinline__ void store_out4(void *O, int64_t elem_off, int out_dtype, float a, float b,
                                            float c, float d) {
-    // (outputs are written once and not read again by these kernels: stored with the streaming hint,
-    // so that they do not push K and V out of the XCD's L2)
     if (out_dtype == SMHA_F32) {
         f32x4 v = {a, b, c, d};
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(O) + elem_off));
+        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(O) + elem_off) = v;
     } else if (out_dtype == SMHA_BF16) {
         u32x2 v = {pack2<true>(a, b), pack2<true>(c, d)};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off));
+        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off) = v;
     } else {
         u32x2 v = {pack2<false>(a, b), pack2<false>(c, d)};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off));
+        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off) = v;
     }
 }
 
@@ -208,10 +206,10 @@ template <int OUT>  // smha_dtype_t of the output
 __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float b, float c, float d) {
     if constexpr (OUT == SMHA_F32) {
         f32x4 v = {a, b, c, d};
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(O) + elem_off));
+        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(O) + elem_off) = v;
     } else {
         u32x2 v = {pack2<OUT == SMHA_BF16>(a, b), pack2<OUT == SMHA_BF16>(c, d)};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off));
+        *reinterpret_cast<u32x2 *>(reinterpret_cast<uint16_t *>(O) + elem_off) = v;
     }
 }
 
