@@ -18,9 +18,12 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 
 def _time(fn, stream, torch, steps, warmup, graph=False):
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
+    import time
+    t_end = time.perf_counter() + 0.03  # the chip's clocks need about 30 ms of load to settle
+    while time.perf_counter() < t_end:
+        for _ in range(max(warmup, 1)):
+            fn()
+        torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     if graph:
         # 20 calls captured once and replayed: the device's time per call, without the host's call rate
