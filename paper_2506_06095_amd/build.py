@@ -23,6 +23,9 @@ def hipcc() -> str:
 def command(extra=()):
     return [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            # instruction scheduler that keeps memory operations in clauses: 2 % (d = 128) to 7 % (gathered
+            # tiles) faster block kernel than the default, never slower on the five workloads
+            "-mllvm", "-amdgpu-sched-strategy=max-memory-clause",
             "-Wno-unused-command-line-argument",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra,
             *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
