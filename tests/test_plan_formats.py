@@ -202,6 +202,14 @@ def test_error_paths_return_status_codes():
         assert st == 3
 
 
+def test_bench_refuses_more_than_one_gpu_and_says_so():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
 def test_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "smha.h")).read()
     names = set(re.findall(r"\b(smha_[a-z_0-9]+)\s*\(", text))
