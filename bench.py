@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # very command, scaled by what the same counters read for a 256 MiB device copy (FETCH_SIZE x2.0,
 # WRITE_SIZE x1.0 on this machine).  Source: the summaries under profiles/ named for kernel and workload.
 MEASURED_TRAFFIC = {
-    ("cfg5_bigbird_8k", "block"): {"read_bytes": 302.2e6, "write_bytes": 84.5e6},
+    ("cfg5_bigbird_8k", "block"): {"read_bytes": 292.2e6, "write_bytes": 84.3e6},
     ("cfg4_random_blocks", "block"): {"read_bytes": 50.9e6, "write_bytes": 23.1e6},
     ("cfg3_strided_causal", "row"): {"read_bytes": 59.1e6, "write_bytes": 16.8e6},
     ("cfg3_strided_causal", "block"): {"read_bytes": 71.0e6, "write_bytes": 26.2e6},
