@@ -338,6 +338,41 @@ def test_fine_work_items_cut_every_list_to_16_steps_and_number_their_partials():
         assert np.array_equal(p.export("kernel_items"), p.export("kernel_items_fine"))
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_kernel_work_lists_of_random_masks_cover_each_unmasked_entry_once_and_order_every_item(seed):
+    """Random mixtures of bands, long rows, scattered columns and blocks, square and rectangular, ragged sizes."""
+    rng = np.random.default_rng(500 + seed)
+    Sq = int(rng.integers(1, 700))
+    Sk = Sq if rng.random() < 0.6 else int(rng.integers(1, 1500))
+    Hm = int(rng.integers(1, 3))
+    i, j = np.arange(Sq)[:, None], np.arange(Sk)[None, :]
+    masks = np.zeros((1, Hm, Sq, Sk), dtype=np.uint8)
+    for h in range(Hm):
+        m = np.zeros((Sq, Sk), dtype=bool)
+        if rng.random() < 0.7:
+            m |= np.abs(i * Sk // max(Sq, 1) - j) <= int(rng.integers(0, 90))
+        if rng.random() < 0.5:
+            m |= (i < int(rng.integers(0, 70))) | (j < int(rng.integers(0, 20)))
+        if rng.random() < 0.5:
+            m |= rng.random((Sq, Sk)) < rng.choice([0.002, 0.02])
+        if rng.random() < 0.5:
+            blk = rng.random(((Sq + 63) // 64, (Sk + 63) // 64)) < 0.15
+            m |= np.kron(blk, np.ones((64, 64), dtype=bool))[:Sq, :Sk]
+        if rng.random() < 0.3:
+            m &= j <= i * Sk // max(Sq, 1)
+        masks[0, h] = m
+    make = smha.Plan.from_dense if Sq == Sk else smha.Plan.from_dense_rect
+    with make(masks, device_id=-2, force=smha.SMHA_KERNEL_BLOCK, no_gather=bool(seed % 3 == 0)) as plan:
+        assert plan.info()["nnz"] == int(masks.sum())
+        for mi in range(Hm):
+            for which, longest in (("kernel_items", 64), ("kernel_items_fine", 16)):
+                cnt = mask_from_kernel_lists(plan, mi, Sq, Sk, which, longest)
+                assert np.array_equal(cnt[:Sq, :Sk], masks[0, mi].astype(np.int32)), (seed, mi, which)
+                assert cnt[Sq:].sum() == 0 and cnt[:, Sk:].sum() == 0
+        for B, H, slots, fine in ((1, Hm, 64, False), (3, Hm if Hm > 1 else 5, 32, True)):
+            check_work_order(plan, B, H, slots, fine=fine)
+
+
 @pytest.mark.parametrize("name", ["cfg3", "strided_cols", "scattered", "rect_scattered", "mixed_long_rows"])
 def test_kernel_work_lists_with_gathered_tiles_cover_the_mask_exactly_once(name):
     rng = np.random.default_rng(11)
