@@ -125,8 +125,9 @@ typedef struct {
  *   BITMAP_IT8 uint64[n_part][64] (block == 64 only): the paper's inner-tile layout, word
  *     ic*8+ir = 8x8 inner tile (ir, ic) (column-major over inner tiles), bit 8*r+c = entry (r,c)
  * The block kernel's own work lists (for inspection and tests; UNSUPPORTED if the plan has none):
- *   KERNEL_ITEMS int32[n_items of this mask][8]: {128-row group, first entry, end entry, scratch slot
- *     or -1, first gathered tile, gathered tiles, 0, 0}
+ *   KERNEL_ITEMS int32[n_items of this mask][8]: {128-row group, first entry, end entry, workspace slot
+ *     or -1, first gathered tile, gathered tiles, split group (index among this mask's split groups)
+ *     or -1, 0}
  *   KERNEL_ITEMS_FINE: the same groups cut to at most 16 entries per item; smha_forward walks these
  *     instead when the call has too few items to fill the chip (few heads, long lists), so that the
  *     longest list does not set the launch's duration
@@ -205,13 +206,16 @@ smha_status_t smha_plan_export(const smha_plan_t *plan, int mask_index, smha_exp
  *                   each tensor must span less than 2 GiB (UNSUPPORTED otherwise).
  *   scale           <= 0 selects 1/sqrt(d)
  *   kernel          AUTO = the plan's choice; ROW/BLOCK need that format in the plan
- * The plan is read-only here except for two device buffers the block kernel uses: the
- * work order (which workgroup takes which work item; made and uploaded at the first call
- * with a given B, H and d; the eight most recent combinations are kept) and a scratch buffer for query
- * tiles that are split along keys (grown on the first call that needs more room).  Both
- * steps call hipMalloc, so two forwards on one plan must not overlap on different
- * streams, and a call that may take either step must not be captured into a HIP graph
- * (warm up once with the same B, H and d first).
+ * What the block kernel needs per call shape (B, H, d) beyond the plan's index arrays -- the work
+ * order and the workspaces of split 128-row groups, see smha_plan_prepare -- is made by that
+ * function or, if the shape was never prepared, by the first forward that uses it (that one call
+ * allocates device memory and copies to it, so it must not be captured into a HIP graph; every later
+ * call, and every call with a prepared shape, allocates, frees and synchronises nothing).  Nothing
+ * made for a shape is freed or moved before smha_plan_destroy, so captured graphs and queued
+ * launches stay valid whatever other shapes are used later.  Forwards on one plan may overlap on
+ * different streams: successive calls with one shape take its 4 workspaces in turn, so up to 4 of
+ * them may be in flight at once (a fifth would share the first one's workspace: serialise it
+ * behind that call).
  * Errors: INVALID_ARG, UNSUPPORTED (d, dtype, alignment, missing format, more than 2^28
  * work items in one call), SHAPE, ALLOC, HIP. */
 smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K, const void *V,
@@ -220,6 +224,17 @@ smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K
                            const int64_t k_strides[3], const int64_t v_strides[3],
                            const int64_t o_strides[3], float scale, smha_kernel_t kernel,
                            void *hip_stream);
+
+/* Makes, once, everything smha_forward needs for calls with this batch size, head count and head
+ * size on a plan that runs the block-wise kernel (Sec. 4.2.2): the work order (which workgroup
+ * takes which work item, see smha_plan_work_order) and 4 workspaces that hold the partial results
+ * of 128-row groups whose tile lists were split between workgroups (those are merged inside the
+ * same launch by whichever part finishes last) -- B*H * (split parts per head) * (128 d + 512)
+ * floats each; plans that split nothing get none.  Allocates device memory and copies to it
+ * (blocking); call it outside stream capture, on the plan's device.  Calling it again for the
+ * same shape does nothing; plans that run the row-wise kernel need nothing and return SMHA_OK.
+ * Errors: INVALID_ARG, UNSUPPORTED (d, more than 2^28 work items), SHAPE, ALLOC, HIP. */
+smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H, int d);
 
 /* The block kernel's work order for B x H heads when workgroups_per_xcd workgroups are
  * resident on each of the chip's 8 XCDs (smha_forward uses 2 per compute unit at d = 128,

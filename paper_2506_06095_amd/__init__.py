@@ -9,4 +9,4 @@ from .binding import (  # noqa: F401
     SMHA_SELECTOR_CALIBRATED, SMHA_SELECTOR_PAPER_EQ1, Plan, SmhaError, library_path,
     smha_forward, smha_kernel_name, smha_plan_destroy, smha_plan_export, smha_plan_from_dense,
     smha_plan_from_dense_rect,
-    smha_plan_from_desc, smha_plan_info, smha_plan_work_order, smha_status_string)
+    smha_plan_from_desc, smha_plan_info, smha_plan_prepare, smha_plan_work_order, smha_status_string)

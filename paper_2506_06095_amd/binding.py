@@ -92,6 +92,8 @@ def _load():
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                  C.POINTER(C.c_int64), C.c_float, C.c_int, vp]
     lib.smha_forward.restype = C.c_int
+    lib.smha_plan_prepare.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.smha_plan_prepare.restype = C.c_int
     lib.smha_plan_work_order.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
                                          C.POINTER(C.c_size_t), C.POINTER(C.c_int)]
     lib.smha_plan_work_order.restype = C.c_int
@@ -214,6 +216,13 @@ def smha_plan_work_order(plan: int, B: int, H: int, workgroups_per_xcd: int, fin
     return out, per.value
 
 
+def smha_plan_prepare(plan: int, B: int, H: int, d: int) -> None:
+    """Make the work order and workspaces for calls with this batch size, head count and head size."""
+    st = _load().smha_plan_prepare(C.c_void_p(plan), B, H, d)
+    if st != 0:
+        raise SmhaError(st, "smha_plan_prepare")
+
+
 def smha_plan_destroy(plan: Optional[int]) -> None:
     if plan:
         _load().smha_plan_destroy(C.c_void_p(plan))
@@ -302,6 +311,9 @@ class Plan:
 
     def work_order(self, B: int, H: int, workgroups_per_xcd: int, fine: bool = False):
         return smha_plan_work_order(self.handle, B, H, workgroups_per_xcd, fine)
+
+    def prepare(self, B: int, H: int, d: int) -> None:
+        smha_plan_prepare(self.handle, B, H, d)
 
     def forward(self, Q, K, V, out=None, out_dtype=None, scale: float = 0.0,
                 kernel: int = SMHA_KERNEL_AUTO, stream=None):

@@ -47,25 +47,24 @@ struct FwdParams {
     // positions r, r + gridDim.x / 8, ... until the list ends or a pair with batch*head < 0 comes up.
     // order_hdr = {start of each XCD's list (8), length (8)}
     const int32_t *order, *order_hdr;
-    int n_work;  // 8 * the longest list (bounds the development stamps)
+    int n_work;  // 8 * the longest list
     int per_xcd; // workgroups per XCD the order was made for (host side: the grid is 8 times this)
     const UEntry *uent;
     const int32_t *gidx;  // gathered tiles: 64 key numbers each
     int n_gidx;           // entries of gidx
     const uint64_t *kt_bitmap;
     int bmp_spare;  // index of an all-zero spare bitmap block (what fetch_word falls back to for a tile without a bitmap)
+    // split 128-row groups: workspace slots of 128 D + 512 floats per (batch*head), arrival counters
+    // (4 per (batch*head, split group), zero between launches), and the groups' descriptions
     float *scratch;
-    int max_slots;
+    uint32_t *counters;
+    int max_slots, max_splits;
     const SplitRow *split_rows;
     const int32_t *split_off, *split_cnt;
     // row path
     const int32_t *row_ptr, *col_idx;
     const int64_t *col_off;
     int wgs_per_bh;
-#ifdef SMHA_DEV
-    int dbg;  // development-only switches (timing experiments)
-    unsigned long long *stamps;  // [n_work][8] cycle stamps
-#endif
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -213,13 +212,6 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
     }
 }
 
-#ifdef SMHA_DEV
-#define STAMP(k) do { if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)wg * 8 + (k)] = __builtin_readcyclecounter(); } while (0)
-#define PHASE(k) do { if (p.dbg & 256) { unsigned long long now = __builtin_readcyclecounter(); ph[k] += now - tprev; tprev = now; } } while (0)
-#else
-#define STAMP(k) do { } while (0)
-#define PHASE(k) do { } while (0)
-#endif
 
 // GATHER: the plan holds gathered tiles (staged rows that come from arbitrary key numbers, see
 // UEntry); plans without any run the instantiation that does not know about them.
@@ -267,7 +259,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // requested right after the current item's last tile, before the current item's output
     // stores, so memory latency of an item's start hides behind the previous item's end.
     struct Work {  // wave-uniform
-        int valid, b, h, bh, qtile, begin, n, slot, col0, code0[2], gid0;  // col0, code0, gid0: the first entry
+        int valid, b, h, bh, qtile, begin, n, slot, split, col0, code0[2], gid0;  // col0, code0, gid0: the first entry
         int gbegin, gcount;
     };
     const int xcd = blockIdx.x & 7, per_xcd = gridDim.x >> 3;
@@ -277,7 +269,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         wk.valid = pos < list_len;
         wk.bh = wk.b = wk.h = 0;
         wk.qtile = wk.begin = wk.n = wk.col0 = wk.gid0 = wk.gbegin = wk.gcount = 0;
-        wk.slot = -1;
+        wk.slot = wk.split = -1;
         wk.code0[0] = wk.code0[1] = -2;
         if (wk.valid) {
             struct Pair { int32_t bh, index; };
@@ -298,6 +290,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                 wk.begin = item.begin;
                 wk.n = item.end - item.begin;
                 wk.slot = item.slot;
+                if (item.slot >= 0) wk.split = uniform_load(&ip->split);
                 const UEntry e0 = uniform_load(p.uent + item.begin);  // (the array ends with a spare entry)
                 wk.col0 = e0.col;
                 wk.gid0 = wk.n > 0 ? e0.gather : 0;
@@ -402,13 +395,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     if (item.valid) start_work(item);
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     while (item.valid) {
-#ifdef SMHA_DEV
-    const int wg = xcd + 8 * pos;
-#endif
-    STAMP(0);
-#ifdef SMHA_DEV
-    unsigned long long ph[7] = {0, 0, 0, 0, 0, 0, 0}, tprev = 0;
-#endif
     // the next item's descriptor: scalar loads that complete under this item's tiles
     pos += per_xcd;
     const Work nxt = fetch_work(pos);
@@ -488,7 +474,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             if (i + PF < 2 * NS) kfrag[i % PF] = *reinterpret_cast<const u32x4 *>(k_addr(i + PF));
             __builtin_amdgcn_sched_barrier(0);
         }
-        PHASE(2);
         // From here to the end of the tile the wave mixes vector-ALU work with its MFMAs: it gets issue
         // priority over waves that are in their pure-MFMA phase, whose MFMAs fill the gaps (measured:
         // 6 % on cfg4 with four waves per SIMD, nothing lost elsewhere).
@@ -569,10 +554,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         float gs = 0.f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) p_pair(0, q, gs);
-        PHASE(1);
 #pragma unroll
         for (int cu = 0; cu < 4; ++cu) {
-            if (cu == 1) PHASE(3);
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) {
                 const int i = cu * NDT + dt;
@@ -596,7 +579,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // and copies between them), land in the other pair, which every wave left at the previous
     // barrier; they are waited for at the barrier that ends tile t.  One loop body; the buffer
     // pair is a run-time offset.
-    STAMP(1);
     e_col = raw_col;
     if constexpr (GATHER) e_gid = raw_gid;
     e_code = lane < n ? ((w >> 1) ? raw_code1 : raw_code0) : -2;
@@ -611,10 +593,6 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     uint64_t word = raw_word;
     __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the slab is read before tile 1 may overwrite it
     __builtin_amdgcn_s_barrier();        // every wave's part of tile 0 is visible
-    STAMP(2);
-#ifdef SMHA_DEV
-    if (p.dbg & 256) tprev = __builtin_readcyclecounter();
-#endif
     for (int t = 0; t < n; ++t) {
         const int par = t & 1;
         const int code_next = entry_code(t + 1);
@@ -624,21 +602,13 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         const uint32_t Kn = smem_base + (par ^ 1) * TB, Vn = smem_base + (2 + (par ^ 1)) * TB;
 #pragma unroll
         for (int i = 0; i < 2 * LPW; ++i) load_piece(i, Kn, Vn);
-        PHASE(0);
         if (code != -2) compute_tile(par * TB, (2 + par) * TB, Kn, Vn, code, word);
-        PHASE(4);
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): tile t+1 landed, own LDS reads done
-        PHASE(6);
         __builtin_amdgcn_s_barrier();        // ... for every wave: tile t+1 visible, tile t free
-        PHASE(5);
         code = code_next;
         word = word_next;
     }
 
-    STAMP(3);
-#ifdef SMHA_DEV
-    if ((p.dbg & 256) && p.stamps && threadIdx.x == 0) { p.stamps[(size_t)wg * 8 + 5] = ph[0] + (ph[1] << 32); p.stamps[(size_t)wg * 8 + 6] = ph[2] + (ph[3] << 32); p.stamps[(size_t)wg * 8 + 7] = ph[4] + (ph[5] << 32); p.stamps[(size_t)wg * 8 + 1] = ph[6]; }
-#endif
     // Every load issued for this item has landed and every wave is past its last LDS read (the
     // last barrier), so the next item's requests can go out now; the output stores follow them.
     // o[dt][r] = O[q = q0 + j][d = 32 dt + 8 (r/4) + 4 hh + r%4]
@@ -697,78 +667,95 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                                     o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
             }
         } else {
-            float *sc = p.scratch + ((size_t)bh * p.max_slots + item.slot) * (size_t)(128 * D + 256);
-            const int row = 32 * w + j;
+            // Part of a split group: the wave's 32 rows of the unnormalised partial result go to the
+            // workspace, register by register (64 consecutive floats per wave instruction), followed by
+            // the rows' running maximum (in units of the exponent) and sum.  Parts run on any XCD and
+            // the XCDs' L2 caches are not coherent with each other, so these stores and the loads
+            // below are device-scope atomic accesses (they go through to memory), and the wave waits for
+            // its stores before it counts itself in: when a counter reads count - 1, every other part's
+            // quarter is in memory.  The wave that finds it so merges all parts in list order (its own
+            // included, re-read: the result does not depend on which part came last) and writes O.
+            constexpr int NR = 16 * NDT;                     // accumulator registers per lane
+            constexpr size_t SLOT = (size_t)(128 * D + 512);  // floats per workspace slot
+            float *mine = p.scratch + ((size_t)bh * p.max_slots + item.slot) * SLOT;
+            auto put = [&](float *ptr, float v) __attribute__((always_inline)) {
+                __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            };
+            auto get = [&](const float *ptr) __attribute__((always_inline)) {
+                return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            };
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    f32x4 v = {o[dt][4 * g4], o[dt][4 * g4 + 1], o[dt][4 * g4 + 2], o[dt][4 * g4 + 3]};
-                    __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(sc + row * D + 32 * dt + 8 * g4 + 4 * hh));  // (read next by the merge kernel, on any XCD)
+                for (int r = 0; r < 16; ++r) put(mine + ((size_t)w * NR + dt * 16 + r) * 64 + lane, o[dt][r]);
+            put(mine + 128 * D + w * 64 + lane, m_run * p.c);  // -inf stays -inf (c > 0)
+            put(mine + 128 * D + 256 + w * 64 + lane, l_tot);
+            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0): the stores above have completed
+            const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
+            const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + item.split);
+            uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + item.split) * 4 + w;
+            uint32_t seen = 0;
+            if (lane == 0) seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            seen = __builtin_amdgcn_readfirstlane(seen);
+            if ((int)seen == sr.count - 1) {
+                if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+                const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * SLOT;
+                float mstar = NEG_INF;
+                for (int c0 = 0; c0 < sr.count; c0 += 8) {  // (eight loads in flight at a time)
+                    float ms[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) ms[u] = get(base + (size_t)min(c0 + u, sr.count - 1) * SLOT + 128 * D + w * 64 + lane);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) mstar = fmaxf(mstar, ms[u]);
                 }
-            if (hh == 0) {
-                sc[128 * D + row] = m_run * p.c;  // -inf stays -inf (c > 0)
-                sc[128 * D + 128 + row] = l_tot;
+                float acc[NR];
+#pragma unroll
+                for (int r = 0; r < NR; ++r) acc[r] = 0.f;
+                float L = 0.f;
+                if (mstar != NEG_INF) {
+                    constexpr int PB = 4;  // parts per batch: their loads are in flight together
+                    const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
+                    for (int c0 = 0; c0 < sr.count; c0 += PB) {
+                        float wgt[PB];
+                        int at[PB];  // float offset of part c0 + u from part 0 (parts past the end: part c0 again, weight 0)
+#pragma unroll
+                        for (int u = 0; u < PB; ++u) {
+                            const bool live = c0 + u < sr.count;
+                            at[u] = (live ? c0 + u : c0) * (int)SLOT;
+                            const float mu = get(base + at[u] + 128 * D + w * 64 + lane);
+                            wgt[u] = live ? fast_exp2(mu - mstar) : 0.f;  // (-inf - finite: 0)
+                            L += wgt[u] * get(base + at[u] + 128 * D + 256 + w * 64 + lane);
+                        }
+#pragma unroll
+                        for (int r0 = 0; r0 < NR; r0 += 8) {
+                            float v[PB][8];
+#pragma unroll
+                            for (int u = 0; u < PB; ++u)
+#pragma unroll
+                                for (int i = 0; i < 8; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
+#pragma unroll
+                            for (int u = 0; u < PB; ++u)
+#pragma unroll
+                                for (int i = 0; i < 8; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
+                        }
+                    }
+                }
+                if (qrow < S) {
+                    const float inv = L > 0.f ? 1.0f / L : 0.f;
+                    const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+#pragma unroll
+                    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+                        for (int g4 = 0; g4 < 4; ++g4)
+                            store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[16 * dt + 4 * g4] * inv, acc[16 * dt + 4 * g4 + 1] * inv,
+                                        acc[16 * dt + 4 * g4 + 2] * inv, acc[16 * dt + 4 * g4 + 3] * inv);
+                }
             }
         }
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     }
     item = nxt;
-    STAMP(4);
     }  // persistent loop over work items
-}
-
-// Merge the partial (O, m, l) of supertiles that were split along keys.  One workgroup per
-// (split supertile, 16-row slab, batch*head); thread = (row, 4 output columns).
-template <int D, int OUT>
-__global__ void __launch_bounds__(16 * (D / 4)) smha_block_combine(const FwdParams p) {
-    const int bh = blockIdx.z;
-    const int b = bh / p.H, h = bh - b * p.H;
-    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
-    if ((int)blockIdx.x >= p.split_cnt[mask]) return;
-    const SplitRow sr = p.split_rows[p.split_off[mask] + blockIdx.x];
-    const size_t stride = (size_t)(128 * D + 256);
-    const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * stride;
-    const int row = blockIdx.y * 16 + threadIdx.x / (D / 4), dq = threadIdx.x % (D / 4);
-    const int qrow = sr.qtile * 128 + row;
-    if (qrow >= p.S) return;
-    // Loads go out in batches of 8 partials, all requested before the first is used: the kernel is
-    // a chain of memory latencies otherwise (partials were written by other XCDs, so they miss L2).
-    constexpr int NB = 8;
-    const float NEG_INF = -__builtin_inff();
-    float mstar = NEG_INF;
-    for (int c0 = 0; c0 < sr.count; c0 += NB) {
-        float ms[NB];
-#pragma unroll
-        for (int u = 0; u < NB; ++u) ms[u] = c0 + u < sr.count ? base[(c0 + u) * stride + 128 * D + row] : NEG_INF;
-#pragma unroll
-        for (int u = 0; u < NB; ++u) mstar = fmaxf(mstar, ms[u]);
-    }
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float L = 0.f;
-    if (mstar != NEG_INF) {
-        for (int c0 = 0; c0 < sr.count; c0 += NB) {
-            float ms[NB], ls[NB];
-            f32x4 vs[NB];
-#pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const bool live = c0 + u < sr.count;
-                const float *part = base + (live ? c0 + u : c0) * stride;
-                ms[u] = live ? part[128 * D + row] : NEG_INF;  // (weight 0 past the end)
-                ls[u] = part[128 * D + 128 + row];
-                vs[u] = *reinterpret_cast<const f32x4 *>(part + row * D + 4 * dq);
-            }
-#pragma unroll
-            for (int u = 0; u < NB; ++u) {
-                const float wgt = fast_exp2(ms[u] - mstar);
-                L += wgt * ls[u];
-                acc += vs[u] * wgt;
-            }
-        }
-    }
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
-    store4<OUT>(p.O, b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s + 4 * dq, acc[0] * inv, acc[1] * inv,
-                acc[2] * inv, acc[3] * inv);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1125,17 +1112,17 @@ void release_device(smha_plan *p) {
     DeviceArrays &d = p->dev;
     void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap,
                     d.items[0], d.item_off[0], d.item_cnt[0], d.split_rows[0], d.split_off[0], d.split_cnt[0],
-                    d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1],
-                    p->d_scratch,
-                    p->orders[0].dev, p->orders[1].dev, p->orders[2].dev, p->orders[3].dev,
-                    p->orders[4].dev, p->orders[5].dev, p->orders[6].dev, p->orders[7].dev};
-    static_assert(smha_plan::kOrders == 8, "the list above names every cached work order");
+                    d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1]};
     for (void *q : ptrs)
         if (q) (void)hipFree(q);
     d = DeviceArrays{};
-    p->d_scratch = nullptr;
-    p->scratch_bytes = 0;
-    for (smha_plan::Order &o : p->orders) o = smha_plan::Order{};
+    for (smha_plan::Prepared *pr : p->prepared) {
+        if (pr->order) (void)hipFree(pr->order);
+        for (void *q : pr->ws)
+            if (q) (void)hipFree(q);
+        delete pr;
+    }
+    p->prepared.clear();
     p->device = -1;
     (void)hipSetDevice(prev);
 }
@@ -1150,8 +1137,7 @@ using namespace smha;
 static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0 && s[2] > 0); }
 
 template <int D, bool BF16, int OUT>
-static hipError_t launch_block_out(const smha_plan *plan, const WorkLists &wl, FwdParams &fp, hipStream_t stream) {
-    const int BH = fp.B * fp.H;
+static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     if (fp.n_work == 0) return hipSuccess;
     // the grid fills the chip once (two workgroups fit a CU at d = 128, four at d = 64: LDS and
     // registers); the work order was made for exactly this many workgroups
@@ -1160,20 +1146,13 @@ static hipError_t launch_block_out(const smha_plan *plan, const WorkLists &wl, F
         hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true>), dim3(grid), dim3(256), 0, stream, fp);
     else
         hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false>), dim3(grid), dim3(256), 0, stream, fp);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (wl.max_split_rows > 0) {
-        hipLaunchKernelGGL((smha_block_combine<D, OUT>), dim3(wl.max_split_rows, 8, BH), dim3(16 * (D / 4)), 0,
-                           stream, fp);
-        e = hipGetLastError();
-    }
-    return e;
+    return hipGetLastError();
 }
 
 template <int D, bool BF16>
-static hipError_t launch_block(const smha_plan *plan, const WorkLists &wl, FwdParams &fp, hipStream_t stream) {
-    if (fp.out_dtype == SMHA_F32) return launch_block_out<D, BF16, SMHA_F32>(plan, wl, fp, stream);
-    return launch_block_out<D, BF16, BF16 ? SMHA_BF16 : SMHA_F16>(plan, wl, fp, stream);
+static hipError_t launch_block(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
+    if (fp.out_dtype == SMHA_F32) return launch_block_out<D, BF16, SMHA_F32>(plan, fp, stream);
+    return launch_block_out<D, BF16, BF16 ? SMHA_BF16 : SMHA_F16>(plan, fp, stream);
 }
 
 template <int D, bool BF16>
@@ -1190,6 +1169,100 @@ static hipError_t launch_row(const smha_plan *plan, FwdParams &fp, hipStream_t s
     else
         hipLaunchKernelGGL((smha_row_fwd<D, BF16, 1>), dim3(grid), dim3(256), 0, stream, fp);
     return hipGetLastError();
+}
+
+// Which grain of work items a call walks: the coarse lists unless they leave more than half of the
+// chip's workgroup slots empty for this batch and head count (then the longest list would be the launch).
+static int grain_for(const smha_plan *plan, int B, int H, int d) {
+    if (!plan->fine_differs) return 0;
+    int64_t n_items = 0;
+    const WorkLists &w0 = plan->lists[0];
+    if (plan->Bm == 1 && plan->Hm == 1)
+        n_items = (int64_t)B * H * w0.item_cnt[0];
+    else
+        for (int bh = 0; bh < B * H; ++bh)
+            n_items += w0.item_cnt[(plan->Bm > 1 ? bh / H : 0) * plan->Hm + (plan->Hm > 1 ? bh % H : 0)];
+    return 2 * n_items < (int64_t)(d == 64 ? 4 : 2) * plan->n_cu ? 1 : 0;
+}
+
+// The work order and workspaces for a call shape: found, or made now (allocates and copies; nothing
+// that exists is freed or moved).  *ws receives the workspace for this call (null if the plan splits
+// no group).
+static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, int lvl,
+                                  const smha_plan::Prepared **out, void **ws) {
+    std::lock_guard<std::mutex> lock(plan->prepared_mutex);
+    smha_plan::Prepared *hit = nullptr;
+    for (smha_plan::Prepared *q : plan->prepared)
+        if (q->B == B && q->H == H && q->d == d && q->lvl == lvl) hit = q;
+    if (!hit) {
+        const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
+        if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
+        std::vector<int32_t> table;
+        int per_xcd = 0;
+        const int slots = (d == 64 ? 4 : 2) * plan->n_cu / 8;  // workgroups that fit an XCD at once
+        smha_plan::Prepared *q = nullptr;
+        try {
+            build_work_order(plan, lvl, B, H, slots, table, per_xcd);
+            q = new smha_plan::Prepared();
+        } catch (const std::bad_alloc &) {
+            return SMHA_ERR_ALLOC;
+        }
+        q->B = B; q->H = H; q->d = d; q->lvl = lvl; q->per_xcd = per_xcd;
+        for (int x = 0; x < 8; ++x) q->longest = std::max(q->longest, table[8 + x]);
+        bool ok = hipMalloc((void **)&q->order, table.size() * sizeof(int32_t)) == hipSuccess &&
+                  hipMemcpy(q->order, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+        if (ok && wl.max_slots > 0) {
+            q->ws_bytes = workspace_bytes(plan, lvl, B, H, d, &q->counters_at);
+            // (the counters start at zero and every launch leaves them at zero; the copy has completed on return)
+            const std::vector<uint32_t> zeros((q->ws_bytes - q->counters_at) / sizeof(uint32_t), 0u);
+            for (int i = 0; ok && i < smha_plan::kCallSlots; ++i)
+                ok = hipMalloc(&q->ws[i], q->ws_bytes) == hipSuccess &&
+                     hipMemcpy((char *)q->ws[i] + q->counters_at, zeros.data(), zeros.size() * sizeof(uint32_t),
+                               hipMemcpyHostToDevice) == hipSuccess;
+        }
+        if (ok) {
+            try {
+                plan->prepared.push_back(q);
+            } catch (const std::bad_alloc &) {
+                ok = false;
+            }
+        }
+        if (!ok) {
+            (void)hipGetLastError();
+            if (q->order) (void)hipFree(q->order);
+            for (void *w : q->ws)
+                if (w) (void)hipFree(w);
+            delete q;
+            return SMHA_ERR_ALLOC;
+        }
+        hit = q;
+    }
+    *out = hit;
+    *ws = hit->ws_bytes ? hit->ws[hit->next++ % smha_plan::kCallSlots] : nullptr;
+    return SMHA_OK;
+}
+
+static smha_status_t check_shape(const smha_plan *plan, int B, int H, int d) {
+    if (!plan || B < 1 || H < 1) return SMHA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return SMHA_ERR_UNSUPPORTED;
+    if ((plan->Bm != 1 && plan->Bm != B) || (plan->Hm != 1 && plan->Hm != H)) return SMHA_ERR_SHAPE;
+    if ((int64_t)B * H > (1 << 24)) return SMHA_ERR_UNSUPPORTED;
+    return SMHA_OK;
+}
+
+extern "C" smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H, int d) {
+    const smha_status_t st = check_shape(plan, B, H, d);
+    if (st != SMHA_OK) return st;
+    if (!plan->has_block) return SMHA_OK;  // the row kernel needs nothing per shape
+    if (plan->device < 0) return SMHA_ERR_HIP;
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess || cur != plan->device) {
+        (void)hipGetLastError();
+        return SMHA_ERR_HIP;
+    }
+    const smha_plan::Prepared *pr = nullptr;
+    void *ws = nullptr;
+    return prepared_for(plan, B, H, d, grain_for(plan, B, H, d), &pr, &ws);
 }
 
 extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K,
@@ -1241,19 +1314,7 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
-    // Which grain of work items: the coarse lists unless they leave more than half of the chip's
-    // workgroup slots empty for this batch and head count (then the longest list would be the launch).
-    int lvl = 0;
-    if (plan->fine_differs) {
-        int64_t n_items = 0;
-        const WorkLists &w0 = plan->lists[0];
-        if (plan->Bm == 1 && plan->Hm == 1)
-            n_items = (int64_t)B * H * w0.item_cnt[0];
-        else
-            for (int bh = 0; bh < B * H; ++bh)
-                n_items += w0.item_cnt[(plan->Bm > 1 ? bh / H : 0) * plan->Hm + (plan->Hm > 1 ? bh % H : 0)];
-        if (2 * n_items < (int64_t)(d == 64 ? 4 : 2) * plan->n_cu) lvl = 1;
-    }
+    const int lvl = grain_for(plan, B, H, d);
     const WorkLists &wl = plan->lists[lvl];
     fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl];
     fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
@@ -1261,87 +1322,25 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
     fp.split_rows = dv.split_rows[lvl]; fp.split_off = dv.split_off[lvl]; fp.split_cnt = dv.split_cnt[lvl];
     fp.row_ptr = dv.row_ptr; fp.col_idx = dv.col_idx; fp.col_off = dv.col_off;
 
-#ifdef SMHA_DEV
-    { const char *dbg = getenv("SMHA_DBG"); fp.dbg = dbg ? atoi(dbg) : 0;
-      const char *st = getenv("SMHA_STAMPS"); fp.stamps = st ? (unsigned long long *)strtoull(st, nullptr, 0) : nullptr; }
-#endif
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t e = hipSuccess;
     if (which == SMHA_KERNEL_BLOCK) {
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
-        {   // the work order for this batch, head count, grid and grain (the eight most recent are kept)
-            const int slots = (d == 64 ? 4 : 2) * plan->n_cu / 8;  // workgroups that fit an XCD at once
-            std::lock_guard<std::mutex> lock(plan->scratch_mutex);
-            smha_plan::Order *hit = nullptr, *victim = &plan->orders[0];
-            for (smha_plan::Order &o : plan->orders) {
-                if (o.dev && o.B == B && o.H == H && o.slots == slots && o.lvl == lvl) hit = &o;
-                if (!o.dev || (victim->dev && o.last_use < victim->last_use)) victim = &o;
-            }
-            if (!hit) {
-                std::vector<int32_t> table;
-                int per_xcd = 0;
-                build_work_order(plan, lvl, B, H, slots, table, per_xcd);
-                if (victim->dev) {
-                    // earlier launches may still be reading the table that makes room
-                    if (hipDeviceSynchronize() != hipSuccess || hipFree(victim->dev) != hipSuccess) {
-                        (void)hipGetLastError();
-                        return SMHA_ERR_HIP;
-                    }
-                    *victim = smha_plan::Order{};
-                }
-                void *ptr = nullptr;
-                if (hipMalloc(&ptr, table.size() * sizeof(int32_t)) != hipSuccess) {
-                    (void)hipGetLastError();
-                    return SMHA_ERR_ALLOC;
-                }
-                if (hipMemcpy(ptr, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
-                    (void)hipGetLastError();
-                    (void)hipFree(ptr);
-                    return SMHA_ERR_HIP;
-                }
-                hit = victim;
-                hit->dev = (int32_t *)ptr;
-                hit->B = B;
-                hit->H = H;
-                hit->slots = slots;
-                hit->lvl = lvl;
-                hit->per_xcd = per_xcd;
-                hit->longest = 0;
-                for (int x = 0; x < 8; ++x) hit->longest = std::max(hit->longest, table[8 + x]);
-            }
-            hit->last_use = ++plan->order_clock;
-            fp.order_hdr = hit->dev;
-            fp.order = hit->dev + 16;
-            fp.n_work = 8 * hit->longest;
-            fp.per_xcd = hit->per_xcd;
-        }
-        if (wl.max_slots > 0) {
-            const size_t need = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 256) * sizeof(float);
-            std::lock_guard<std::mutex> lock(plan->scratch_mutex);
-            if (need > plan->scratch_bytes) {
-                if (plan->d_scratch) {
-                    // earlier launches may still be reading the old buffer
-                    if (hipDeviceSynchronize() != hipSuccess || hipFree(plan->d_scratch) != hipSuccess) {
-                        (void)hipGetLastError();
-                        return SMHA_ERR_HIP;
-                    }
-                    plan->d_scratch = nullptr;
-                    plan->scratch_bytes = 0;
-                }
-                void *ptr = nullptr;
-                if (hipMalloc(&ptr, need) != hipSuccess) {
-                    (void)hipGetLastError();
-                    return SMHA_ERR_ALLOC;
-                }
-                plan->d_scratch = (float *)ptr;
-                plan->scratch_bytes = need;
-            }
-            fp.scratch = plan->d_scratch;
-        }
+        const smha_plan::Prepared *pr = nullptr;
+        void *ws = nullptr;
+        const smha_status_t st = prepared_for(plan, B, H, d, lvl, &pr, &ws);
+        if (st != SMHA_OK) return st;
+        fp.order_hdr = pr->order;
+        fp.order = pr->order + 16;
+        fp.n_work = 8 * pr->longest;
+        fp.per_xcd = pr->per_xcd;
+        fp.scratch = (float *)ws;
+        fp.counters = ws ? (uint32_t *)((char *)ws + pr->counters_at) : nullptr;
+        fp.max_splits = wl.max_split_rows;
         if (d == 64)
-            e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, wl, fp, stream) : launch_block<64, false>(plan, wl, fp, stream);
+            e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, fp, stream) : launch_block<64, false>(plan, fp, stream);
         else
-            e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, wl, fp, stream) : launch_block<128, false>(plan, wl, fp, stream);
+            e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, fp, stream) : launch_block<128, false>(plan, fp, stream);
     } else {
         if (d == 64)
             e = in_dtype == SMHA_BF16 ? launch_row<64, true>(plan, fp, stream) : launch_row<64, false>(plan, fp, stream);

@@ -596,8 +596,8 @@ smha_status_t finish_plan(smha_plan *p) {
                 std::vector<Item> items;
                 std::vector<SplitRow> splits;
                 int32_t slots = 0;
-                auto make_item = [&](int sp, int32_t b, int32_t e, int32_t slot) {
-                    Item it{sp, b, e, slot, 0, 0, {0, 0}};
+                auto make_item = [&](int sp, int32_t b, int32_t e, int32_t slot, int32_t split = -1) {
+                    Item it{sp, b, e, slot, 0, 0, split, 0};
                     for (int32_t x = b; x < e; ++x)
                         if (p->h_uent[x].gather > 0) {
                             if (!it.gcount) it.gbegin = p->h_uent[x].gather - 1;
@@ -637,7 +637,8 @@ smha_status_t finish_plan(smha_plan *p) {
                         continue;
                     }
                     splits.push_back({sp, slots, n_parts, 0});
-                    for (int c = 0; c < n_parts; ++c) items.push_back(make_item(sp, cuts[c], cuts[c + 1], slots++));
+                    for (int c = 0; c < n_parts; ++c)
+                        items.push_back(make_item(sp, cuts[c], cuts[c + 1], slots++, (int32_t)splits.size() - 1));
                 }
                 std::stable_sort(items.begin(), items.end(), [](const Item &a, const Item &b) {
                     return (a.end - a.begin) > (b.end - b.begin);
@@ -710,6 +711,17 @@ smha_status_t finish_plan(smha_plan *p) {
         if (dev < 0) return SMHA_OK;  // host-only plan; forward will report SMHA_ERR_HIP
     }
     return upload_plan(p, dev);
+}
+
+// One workspace of the block kernel for a call shape: per (batch*head) max_slots partial results of
+// 128 rows (O, then running maximum and sum per row, each written per wave: 128 d + 512 floats), then
+// four arrival counters (one per 32-row quarter) per (batch*head, split group).
+size_t workspace_bytes(const smha_plan *plan, int lvl, int B, int H, int d, size_t *counters_at) {
+    const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
+    const size_t partials = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 512) * sizeof(float);
+    const size_t at = (partials + 255) / 256 * 256;
+    if (counters_at) *counters_at = at;
+    return at + (size_t)B * H * wl.max_split_rows * 4 * sizeof(uint32_t);
 }
 
 // The block kernel's work order for B x H heads on `slots` resident workgroups per XCD.  Items

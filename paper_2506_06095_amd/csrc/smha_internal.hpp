@@ -44,11 +44,13 @@ struct UEntry {
 
 // One workgroup's job: supertile `qtile`, union entries [begin, end).  slot < 0: the item
 // covers the whole list and writes O directly; slot >= 0: it writes an unnormalised partial
-// (O, m, l) of 128 rows to that scratch slot.  Its gathered tiles are the gcount consecutive
-// blocks of key numbers starting at block gbegin (at most kMaxGatherPerItem).
+// (O, m, l) of 128 rows to that workspace slot, and `split` is the index (within the mask) of the
+// SplitRow that names all parts of its supertile; whichever part finishes last merges them.
+// Its gathered tiles are the gcount consecutive blocks of key numbers starting at block gbegin
+// (at most kMaxGatherPerItem).
 struct Item {
     int32_t qtile, begin, end, slot;
-    int32_t gbegin, gcount, pad[2];
+    int32_t gbegin, gcount, split, pad;
 };
 constexpr int kMaxGatherPerItem = 16;
 // a tile with at most this many used key columns is repacked (32 or 48 save a quarter of the steps
@@ -114,21 +116,22 @@ struct smha_plan {
     int n_cu = 256;   // compute units of that device, rounded up to a multiple of 8
     smha::DeviceArrays dev;
 
-    // scratch for split query tiles, grown on demand by smha_forward
-    mutable std::mutex scratch_mutex;
-    mutable float *d_scratch = nullptr;
-    mutable size_t scratch_bytes = 0;
-    // The block kernel's work orders (same mutex), one per (batch, heads, workgroups per XCD, grain)
-    // seen, the eight most recent kept: 16 header words (start and length of each XCD's list), then
-    // (batch*head, item index) pairs.
-    struct Order {
-        int B = 0, H = 0, slots = 0, lvl = 0, per_xcd = 0, longest = 0;
-        int32_t *dev = nullptr;
-        uint64_t last_use = 0;
+    // What the block kernel needs for one call shape (batch, heads, head size): the work order (16
+    // header words: start and length of each XCD's list; then (batch*head, item index) pairs) and
+    // kCallSlots workspaces (partial results of split 128-row groups, then their arrival counters),
+    // handed to successive calls in turn so that forwards in flight on different streams do not
+    // share one.  Made by smha_plan_prepare (or by the first forward with that shape) and kept until
+    // the plan is destroyed: a launch that is still queued, or a captured graph, never loses them.
+    static constexpr int kCallSlots = 4;
+    struct Prepared {
+        int B = 0, H = 0, d = 0, lvl = 0, per_xcd = 0, longest = 0;
+        int32_t *order = nullptr;
+        size_t ws_bytes = 0, counters_at = 0;  // one workspace; byte offset of its counters
+        void *ws[kCallSlots] = {nullptr, nullptr, nullptr, nullptr};
+        unsigned next = 0;
     };
-    static constexpr int kOrders = 8;
-    mutable Order orders[kOrders];
-    mutable uint64_t order_clock = 0;
+    mutable std::mutex prepared_mutex;
+    mutable std::vector<Prepared *> prepared;
 };
 
 namespace smha {
@@ -137,6 +140,8 @@ namespace smha {
 smha_status_t finish_plan(smha_plan *p);      // selector, work lists, concatenation
 // which workgroup of the block kernel takes which item, for B x H heads on `slots` workgroups per XCD
 void build_work_order(const smha_plan *plan, int lvl, int B, int H, int slots, std::vector<int32_t> &table, int &per_xcd);
+// bytes of one workspace for that call shape: partials first, then 4 counters per (batch*head, split group)
+size_t workspace_bytes(const smha_plan *plan, int lvl, int B, int H, int d, size_t *counters_at);
 // device.hip
 smha_status_t upload_plan(smha_plan *p, int device_id);
 void release_device(smha_plan *p);

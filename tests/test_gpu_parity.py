@@ -521,10 +521,11 @@ def test_selected_kernel_wins_on_its_own_ground(torch_mod, smha):
 
 @pytest.mark.parametrize("case", ["split_rows", "gathered"])
 def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
-    """After one eager call (which sizes the plan's scratch buffer) a forward can be captured into a HIP
-    graph: every replay, with other eager work and synchronisation in between, gives the eager result."""
+    """Once its shape is prepared, the very first forward can be captured into a HIP graph: every replay,
+    with eager forwards of the same and of other batch sizes and synchronisation in between, gives the
+    eager result (what the graph points at is never freed or moved by later calls)."""
     torch = torch_mod
-    if case == "split_rows":    # global block rows make a split 128-row group: main kernel + merge kernel
+    if case == "split_rows":    # global block rows make a split 128-row group: partial results merged in the launch
         spec = W.MaskSpec(flags=W.BIGBIRD, block=64, n_window_blocks=3, n_global_blocks=2, n_random_blocks=2, seed=9)
         B, H, S, d = 1, 4, 4096, 128
     else:
@@ -536,7 +537,7 @@ def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
         gen = torch.Generator(device="cuda").manual_seed(5)
         q, k, v = (torch.randn(B, H, S, d, device="cuda", generator=gen).half() for _ in range(3))
         out = torch.empty_like(q)
-        plan.forward(q, k, v, out=out)                      # warm-up: grows the scratch buffer if one is needed
+        plan.prepare(B, H, d)                               # work order and workspaces: nothing is allocated after this
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
@@ -549,6 +550,8 @@ def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
             for t in (q, k, v):
                 t.copy_(torch.randn(B, H, S, d, device="cuda", generator=gen).half())
             eager = plan.forward(q, k, v)                   # eager work between replays
+            nb = B + 1 + rep                                # ... also with batch sizes the plan has not seen yet
+            plan.forward(*(torch.randn(nb, H, S, d, device="cuda", generator=gen).half() for _ in range(3)))
             torch.cuda.synchronize()
             out.zero_()
             graph.replay()
@@ -558,3 +561,33 @@ def test_forward_replays_from_a_hip_graph(torch_mod, smha, case):
         Qb, Kb, Vb = (x.cpu().numpy().view(np.uint16) for x in (q, k, v))
         ref = oracle.masked_attention(*(np.ascontiguousarray(x[:1, :1]) for x in (Qb, Kb, Vb)), "f16", masks)
         check(out[:1, :1].float().cpu().numpy(), ref, f"graph replay {case}")
+
+
+def test_forwards_on_one_plan_overlap_on_two_streams(torch_mod, smha):
+    """Two forwards on one plan (split 128-row groups, so both use a workspace and arrival counters) run at
+    the same time on two streams, several rounds in a row: each call takes its own workspace, so every
+    output equals the one computed alone, and that one matches the oracle."""
+    torch = torch_mod
+    spec = W.MaskSpec(flags=W.BIGBIRD, block=64, n_window_blocks=3, n_global_blocks=2, n_random_blocks=2, seed=3)
+    B, H, S, d = 1, 8, 4096, 128
+    with smha.Plan.from_desc(spec, B, H, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+        assert plan.info()["n_split_rows"] > 0
+        plan.prepare(B, H, d)
+        gen = torch.Generator(device="cuda").manual_seed(11)
+        sets = [[torch.randn(B, H, S, d, device="cuda", generator=gen).half() for _ in range(3)] for _ in range(2)]
+        alone = [plan.forward(*qkv) for qkv in sets]
+        torch.cuda.synchronize()
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for rnd in range(4):
+            outs = [torch.zeros_like(sets[i][0]) for i in range(2)]
+            torch.cuda.synchronize()
+            for rep in range(3):                            # several launches queued per stream
+                for i in range(2):
+                    plan.forward(*sets[i], out=outs[i], stream=streams[i])
+            torch.cuda.synchronize()
+            for i in range(2):
+                assert torch.equal(outs[i], alone[i]), (rnd, i)
+        masks = W.dense_mask(spec, B, H, S)
+        Qb, Kb, Vb = (x.cpu().numpy().view(np.uint16) for x in sets[1])
+        ref = oracle.masked_attention(*(np.ascontiguousarray(x[:1, 3:4]) for x in (Qb, Kb, Vb)), "f16", masks)
+        check(alone[1][:1, 3:4].float().cpu().numpy(), ref, "two streams")
