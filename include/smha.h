@@ -225,6 +225,25 @@ smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K
                            const int64_t o_strides[3], float scale, smha_kernel_t kernel,
                            void *hip_stream);
 
+/* smha_forward for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same result, but the partial
+ * results of split 128-row groups go to an array inside the library's own image (32 MiB per GPU,
+ * held until the process ends) instead of a workspace of the plan, and nothing is ever allocated,
+ * freed or synchronised.  The call shape must have been prepared (smha_plan_prepare, or an earlier
+ * smha_forward with the same B, H, d): UNSUPPORTED otherwise, and also when the shape's workspace
+ * (see smha_plan_prepare) exceeds the 32 MiB.  A small kernel clears the array's arrival counters
+ * ahead of the attention kernel, on the same stream.  Every call on a GPU shares that GPU's one
+ * array: calls that overlap in time on one GPU (two streams, two plans, two threads) race on it and
+ * must be serialised by the caller; calls that follow each other on one stream are fine.  Plans that
+ * split nothing, and the row-wise kernel, do not touch the array.
+ * Errors: as smha_forward, plus UNSUPPORTED as described. */
+smha_status_t smha_forward_static(const smha_plan_t *plan, const void *Q, const void *K, const void *V,
+                                  void *O, int B, int H, int d, smha_dtype_t in_dtype,
+                                  smha_dtype_t out_dtype, const int64_t q_strides[3],
+                                  const int64_t k_strides[3], const int64_t v_strides[3],
+                                  const int64_t o_strides[3], float scale, smha_kernel_t kernel,
+                                  void *hip_stream);
+
 /* Makes, once, everything smha_forward needs for calls with this batch size, head count and head
  * size on a plan that runs the block-wise kernel (Sec. 4.2.2): the work order (which workgroup
  * takes which work item, see smha_plan_work_order) and 4 workspaces that hold the partial results

@@ -7,6 +7,6 @@ the library is missing or no GPU is usable, calls raise.
 from .binding import (  # noqa: F401
     SMHA_BF16, SMHA_F16, SMHA_F32, SMHA_KERNEL_AUTO, SMHA_KERNEL_BLOCK, SMHA_KERNEL_ROW,
     SMHA_SELECTOR_CALIBRATED, SMHA_SELECTOR_PAPER_EQ1, Plan, SmhaError, library_path,
-    smha_forward, smha_kernel_name, smha_plan_destroy, smha_plan_export, smha_plan_from_dense,
+    smha_forward, smha_forward_static, smha_kernel_name, smha_plan_destroy, smha_plan_export, smha_plan_from_dense,
     smha_plan_from_dense_rect,
     smha_plan_from_desc, smha_plan_info, smha_plan_prepare, smha_plan_work_order, smha_status_string)

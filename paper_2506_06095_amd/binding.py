@@ -92,6 +92,8 @@ def _load():
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
                                  C.POINTER(C.c_int64), C.c_float, C.c_int, vp]
     lib.smha_forward.restype = C.c_int
+    lib.smha_forward_static.argtypes = lib.smha_forward.argtypes
+    lib.smha_forward_static.restype = C.c_int
     lib.smha_plan_prepare.argtypes = [vp, C.c_int, C.c_int, C.c_int]
     lib.smha_plan_prepare.restype = C.c_int
     lib.smha_plan_work_order.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t,
@@ -245,8 +247,14 @@ def _strides3(t):
 _DTYPE_CODES = None
 
 
+def smha_forward_static(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
+                        stream=None, _dims=None) -> None:
+    """smha_forward through the entry point that allocates nothing (the shape must be prepared)."""
+    smha_forward(plan, Q, K, V, O, scale, kernel, stream, _dims, _entry="smha_forward_static")
+
+
 def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
-                 stream=None, _dims=None) -> None:
+                 stream=None, _dims=None, _entry="smha_forward") -> None:
     """Q, O: torch CUDA tensors [B,H,S,d]; K, V: [B,H,Sk,d] (S and Sk as in the plan); O in the
     input dtype or float32.  Enqueues on `stream` (default: torch's current stream); does not
     synchronise.  (_dims: the plan's (S, Sk) if the caller already holds them.)"""
@@ -277,11 +285,11 @@ def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_K
     if stream is None:
         stream = torch.cuda.current_stream(Q.device)
     handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
-    st = lib.smha_forward(plan, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, d,
-                          in_code, out_code, _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
-                          float(scale), int(kernel), handle)
+    st = getattr(lib, _entry)(plan, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, d,
+                              in_code, out_code, _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
+                              float(scale), int(kernel), handle)
     if st != 0:
-        raise SmhaError(st, "smha_forward")
+        raise SmhaError(st, _entry)
 
 
 class Plan:
@@ -314,6 +322,13 @@ class Plan:
 
     def prepare(self, B: int, H: int, d: int) -> None:
         smha_plan_prepare(self.handle, B, H, d)
+
+    def forward_static(self, Q, K, V, out, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO, stream=None):
+        if self._dims is None:
+            info = self.info()
+            self._dims = (info["S"], info["Sk"])
+        smha_forward_static(self.handle, Q, K, V, out, scale, kernel, stream, self._dims)
+        return out
 
     def forward(self, Q, K, V, out=None, out_dtype=None, scale: float = 0.0,
                 kernel: int = SMHA_KERNEL_AUTO, stream=None):

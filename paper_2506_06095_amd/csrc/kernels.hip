@@ -1189,11 +1189,12 @@ static int grain_for(const smha_plan *plan, int B, int H, int d) {
 // that exists is freed or moved).  *ws receives the workspace for this call (null if the plan splits
 // no group).
 static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, int lvl,
-                                  const smha_plan::Prepared **out, void **ws) {
+                                  const smha_plan::Prepared **out, void **ws, bool may_allocate = true) {
     std::lock_guard<std::mutex> lock(plan->prepared_mutex);
     smha_plan::Prepared *hit = nullptr;
     for (smha_plan::Prepared *q : plan->prepared)
         if (q->B == B && q->H == H && q->d == d && q->lvl == lvl) hit = q;
+    if (!hit && !may_allocate) return SMHA_ERR_UNSUPPORTED;
     if (!hit) {
         const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
@@ -1265,12 +1266,40 @@ extern "C" smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H
     return prepared_for(plan, B, H, d, grain_for(plan, B, H, d), &pr, &ws);
 }
 
-extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K,
+// Workspace in the library's own image, for callers that cannot allocate: one array per GPU, kept
+// until the process ends.  Host code only ever uses the address hipGetSymbolAddress returns for the
+// current device (the array's name is not a device address on the host side).
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::mutex static_scratch_mutex;
+static void *static_scratch_ptr[kMaxDevices];  // per device, null until asked for
+
+static void *static_scratch_for(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(static_scratch_mutex);
+    if (!static_scratch_ptr[device]) {  // (the caller has made `device` current)
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        static_scratch_ptr[device] = ptr;
+    }
+    return static_scratch_ptr[device];
+}
+
+__global__ void smha_fill_zero(uint32_t *dst, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0u;
+}
+
+static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const void *K,
                                       const void *V, void *O, int B, int H, int d,
                                       smha_dtype_t in_dtype, smha_dtype_t out_dtype,
                                       const int64_t q_strides[3], const int64_t k_strides[3],
                                       const int64_t v_strides[3], const int64_t o_strides[3],
-                                      float scale, smha_kernel_t kernel, void *hip_stream) {
+                                      float scale, smha_kernel_t kernel, void *hip_stream, bool static_ws) {
     if (!plan || !Q || !K || !V || !O || B < 1 || H < 1) return SMHA_ERR_INVALID_ARG;
     if (in_dtype != SMHA_F16 && in_dtype != SMHA_BF16) return SMHA_ERR_UNSUPPORTED;
     if (out_dtype != in_dtype && out_dtype != SMHA_F32) return SMHA_ERR_UNSUPPORTED;
@@ -1328,8 +1357,19 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
         const smha_plan::Prepared *pr = nullptr;
         void *ws = nullptr;
-        const smha_status_t st = prepared_for(plan, B, H, d, lvl, &pr, &ws);
+        const smha_status_t st = prepared_for(plan, B, H, d, lvl, &pr, &ws, !static_ws);
         if (st != SMHA_OK) return st;
+        if (static_ws && pr->ws_bytes) {
+            // the library's own array instead of a workspace of the plan; its counters are cleared by a
+            // small kernel ahead of the launch (the array is shared by every such call on this GPU)
+            if (pr->ws_bytes > kStaticScratchBytes) return SMHA_ERR_UNSUPPORTED;
+            ws = static_scratch_for(plan->device);
+            if (!ws) return SMHA_ERR_HIP;
+            const size_t n = (pr->ws_bytes - pr->counters_at) / sizeof(uint32_t);
+            hipLaunchKernelGGL(smha_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                               (uint32_t *)((char *)ws + pr->counters_at), n);
+            if (hipGetLastError() != hipSuccess) return SMHA_ERR_HIP;
+        }
         fp.order_hdr = pr->order;
         fp.order = pr->order + 16;
         fp.n_work = 8 * pr->longest;
@@ -1348,6 +1388,26 @@ extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, co
             e = in_dtype == SMHA_BF16 ? launch_row<128, true>(plan, fp, stream) : launch_row<128, false>(plan, fp, stream);
     }
     return e == hipSuccess ? SMHA_OK : SMHA_ERR_HIP;
+}
+
+extern "C" smha_status_t smha_forward(const smha_plan_t *plan, const void *Q, const void *K,
+                                      const void *V, void *O, int B, int H, int d,
+                                      smha_dtype_t in_dtype, smha_dtype_t out_dtype,
+                                      const int64_t q_strides[3], const int64_t k_strides[3],
+                                      const int64_t v_strides[3], const int64_t o_strides[3],
+                                      float scale, smha_kernel_t kernel, void *hip_stream) {
+    return forward_impl(plan, Q, K, V, O, B, H, d, in_dtype, out_dtype, q_strides, k_strides, v_strides, o_strides,
+                        scale, kernel, hip_stream, false);
+}
+
+extern "C" smha_status_t smha_forward_static(const smha_plan_t *plan, const void *Q, const void *K,
+                                             const void *V, void *O, int B, int H, int d,
+                                             smha_dtype_t in_dtype, smha_dtype_t out_dtype,
+                                             const int64_t q_strides[3], const int64_t k_strides[3],
+                                             const int64_t v_strides[3], const int64_t o_strides[3],
+                                             float scale, smha_kernel_t kernel, void *hip_stream) {
+    return forward_impl(plan, Q, K, V, O, B, H, d, in_dtype, out_dtype, q_strides, k_strides, v_strides, o_strides,
+                        scale, kernel, hip_stream, true);
 }
 
 extern "C" const char *smha_kernel_name(const smha_plan_t *plan, int d, smha_dtype_t in_dtype,
