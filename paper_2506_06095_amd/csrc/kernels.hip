@@ -15,6 +15,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "smha_internal.hpp"
@@ -47,6 +48,7 @@ struct FwdParams {
     // positions r, r + gridDim.x / 8, ... until the list ends or a pair with batch*head < 0 comes up.
     // order_hdr = {start of each XCD's list (8), length (8)}
     const int32_t *order, *order_hdr;
+    int form;    // 1: (batch*head, item) pairs in `order`; 2: WorkRec records
     int n_work;  // 8 * the longest list
     int per_xcd; // workgroups per XCD the order was made for (host side: the grid is 8 times this)
     const UEntry *uent;
@@ -212,6 +214,98 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
     }
 }
 
+
+// The end of a work item that is one part of a split 128-row group (see Item), for one wave's 32 rows
+// (quarter w of the group): o[dt][r] = unnormalised O[row j][d = 32 dt + 8 (r/4) + 4 hh + r%4], m_c the
+// rows' running maximum in units of the exponent (-inf if none), l_tot their running sum.
+// The partial result goes to the workspace, register by register (64 consecutive floats per wave
+// instruction).  Parts run on any XCD and the XCDs' L2 caches are not coherent with each other, so these
+// stores and the loads below are device-scope atomic accesses (they go through to memory), and the wave
+// waits for its stores before it counts itself in: when the counter reads count - 1, every other part's
+// quarter is in memory.  The wave that finds it so merges all parts in list order (its own included,
+// re-read: the result does not depend on which part came last) and writes O.
+template <int D, int OUT>
+__device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
+                                                  int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
+    constexpr int NDT = D / 32;
+    constexpr int NR = 16 * NDT;                     // accumulator registers per lane
+    constexpr size_t SLOT = (size_t)(128 * D + 512);  // floats per workspace slot
+    const int hh = lane >> 5;
+    const float NEG_INF = -__builtin_inff();
+    float *mine = p.scratch + ((size_t)bh * p.max_slots + slot) * SLOT;
+    auto put = [&](float *ptr, float v) __attribute__((always_inline)) {
+        __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto get = [&](const float *ptr) __attribute__((always_inline)) {
+        return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+#pragma unroll
+    for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) put(mine + ((size_t)w * NR + dt * 16 + r) * 64 + lane, o[dt][r]);
+    put(mine + 128 * D + w * 64 + lane, m_c);
+    put(mine + 128 * D + 256 + w * 64 + lane, l_tot);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0): the stores above have completed
+    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
+    const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + split);
+    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
+    uint32_t seen = 0;
+    if (lane == 0) seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    seen = __builtin_amdgcn_readfirstlane(seen);
+    if ((int)seen != sr.count - 1) return;
+    if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+    const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * SLOT;
+    float mstar = NEG_INF;
+    for (int c0 = 0; c0 < sr.count; c0 += 8) {  // (eight loads in flight at a time)
+        float ms[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ms[u] = get(base + (size_t)min(c0 + u, sr.count - 1) * SLOT + 128 * D + w * 64 + lane);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mstar = fmaxf(mstar, ms[u]);
+    }
+    float acc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
+    float L = 0.f;
+    if (mstar != NEG_INF) {
+        constexpr int PB = 4;  // parts per batch: their loads are in flight together
+        const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
+        for (int c0 = 0; c0 < sr.count; c0 += PB) {
+            float wgt[PB];
+            int at[PB];  // float offset of part c0 + u from part 0 (parts past the end: part c0 again, weight 0)
+#pragma unroll
+            for (int u = 0; u < PB; ++u) {
+                const bool live = c0 + u < sr.count;
+                at[u] = (live ? c0 + u : c0) * (int)SLOT;
+                const float mu = get(base + at[u] + 128 * D + w * 64 + lane);
+                wgt[u] = live ? fast_exp2(mu - mstar) : 0.f;  // (-inf - finite: 0)
+                L += wgt[u] * get(base + at[u] + 128 * D + 256 + w * 64 + lane);
+            }
+#pragma unroll
+            for (int r0 = 0; r0 < NR; r0 += 8) {
+                float v[PB][8];
+#pragma unroll
+                for (int u = 0; u < PB; ++u)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
+#pragma unroll
+                for (int u = 0; u < PB; ++u)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
+            }
+        }
+    }
+    if (qrow < p.S) {
+        const float inv = L > 0.f ? 1.0f / L : 0.f;
+        const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4)
+                store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[16 * dt + 4 * g4] * inv, acc[16 * dt + 4 * g4 + 1] * inv,
+                            acc[16 * dt + 4 * g4 + 2] * inv, acc[16 * dt + 4 * g4 + 3] * inv);
+    }
+}
 
 // GATHER: the plan holds gathered tiles (staged rows that come from arbitrary key numbers, see
 // UEntry); plans without any run the instantiation that does not know about them.
@@ -667,96 +761,15 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                                     o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
             }
         } else {
-            // Part of a split group: the wave's 32 rows of the unnormalised partial result go to the
-            // workspace, register by register (64 consecutive floats per wave instruction), followed by
-            // the rows' running maximum (in units of the exponent) and sum.  Parts run on any XCD and
-            // the XCDs' L2 caches are not coherent with each other, so these stores and the loads
-            // below are device-scope atomic accesses (they go through to memory), and the wave waits for
-            // its stores before it counts itself in: when a counter reads count - 1, every other part's
-            // quarter is in memory.  The wave that finds it so merges all parts in list order (its own
-            // included, re-read: the result does not depend on which part came last) and writes O.
-            constexpr int NR = 16 * NDT;                     // accumulator registers per lane
-            constexpr size_t SLOT = (size_t)(128 * D + 512);  // floats per workspace slot
-            float *mine = p.scratch + ((size_t)bh * p.max_slots + item.slot) * SLOT;
-            auto put = [&](float *ptr, float v) __attribute__((always_inline)) {
-                __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            };
-            auto get = [&](const float *ptr) __attribute__((always_inline)) {
-                return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            };
-#pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) put(mine + ((size_t)w * NR + dt * 16 + r) * 64 + lane, o[dt][r]);
-            put(mine + 128 * D + w * 64 + lane, m_run * p.c);  // -inf stays -inf (c > 0)
-            put(mine + 128 * D + 256 + w * 64 + lane, l_tot);
-            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0): the stores above have completed
-            const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
-            const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + item.split);
-            uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + item.split) * 4 + w;
-            uint32_t seen = 0;
-            if (lane == 0) seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            seen = __builtin_amdgcn_readfirstlane(seen);
-            if ((int)seen == sr.count - 1) {
-                if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
-                const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * SLOT;
-                float mstar = NEG_INF;
-                for (int c0 = 0; c0 < sr.count; c0 += 8) {  // (eight loads in flight at a time)
-                    float ms[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) ms[u] = get(base + (size_t)min(c0 + u, sr.count - 1) * SLOT + 128 * D + w * 64 + lane);
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) mstar = fmaxf(mstar, ms[u]);
-                }
-                float acc[NR];
-#pragma unroll
-                for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-                float L = 0.f;
-                if (mstar != NEG_INF) {
-                    constexpr int PB = 4;  // parts per batch: their loads are in flight together
-                    const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
-                    for (int c0 = 0; c0 < sr.count; c0 += PB) {
-                        float wgt[PB];
-                        int at[PB];  // float offset of part c0 + u from part 0 (parts past the end: part c0 again, weight 0)
-#pragma unroll
-                        for (int u = 0; u < PB; ++u) {
-                            const bool live = c0 + u < sr.count;
-                            at[u] = (live ? c0 + u : c0) * (int)SLOT;
-                            const float mu = get(base + at[u] + 128 * D + w * 64 + lane);
-                            wgt[u] = live ? fast_exp2(mu - mstar) : 0.f;  // (-inf - finite: 0)
-                            L += wgt[u] * get(base + at[u] + 128 * D + 256 + w * 64 + lane);
-                        }
-#pragma unroll
-                        for (int r0 = 0; r0 < NR; r0 += 8) {
-                            float v[PB][8];
-#pragma unroll
-                            for (int u = 0; u < PB; ++u)
-#pragma unroll
-                                for (int i = 0; i < 8; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
-#pragma unroll
-                            for (int u = 0; u < PB; ++u)
-#pragma unroll
-                                for (int i = 0; i < 8; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
-                        }
-                    }
-                }
-                if (qrow < S) {
-                    const float inv = L > 0.f ? 1.0f / L : 0.f;
-                    const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
-#pragma unroll
-                    for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-                        for (int g4 = 0; g4 < 4; ++g4)
-                            store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[16 * dt + 4 * g4] * inv, acc[16 * dt + 4 * g4 + 1] * inv,
-                                        acc[16 * dt + 4 * g4 + 2] * inv, acc[16 * dt + 4 * g4 + 3] * inv);
-                }
-            }
+            finish_split_part<D, OUT>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh, qrow, item.slot, item.split);
         }
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     }
     item = nxt;
     }  // persistent loop over work items
 }
+
+#include "block_fwd2.inc"
 
 // ---------------------------------------------------------------------------------------
 // Row-wise kernel
@@ -1136,9 +1149,29 @@ using namespace smha;
 
 static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0 && s[2] > 0); }
 
+// Which form of the block kernel runs a call: the second form (score and value waves, one workgroup per
+// compute unit) wherever it exists; plans with gathered tiles, and bfloat16 at d = 128 (its LDS does not
+// hold two probability operands per step), run the first.  SMHA_BLOCK_FORM=1 or 2 in the environment
+// (read once) overrides the choice where both exist.
+static int block_form(const smha_plan *plan, int d, bool bf16) {
+    static const int forced = [] {
+        const char *e = getenv("SMHA_BLOCK_FORM");
+        return e ? atoi(e) : 0;
+    }();
+    if (plan->n_gathered > 0 || (bf16 && d == 128)) return 1;
+    return forced == 2 ? 2 : 1;
+}
+static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : 2); }
+
 template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     if (fp.n_work == 0) return hipSuccess;
+    if constexpr (!(BF16 && D == 128)) {
+        if (fp.form == 2) {
+            hipLaunchKernelGGL((smha_block_fwd2<D, BF16, OUT>), dim3(8u * (unsigned)fp.per_xcd), dim3(512), 0, stream, fp);
+            return hipGetLastError();
+        }
+    }
     // the grid fills the chip once (two workgroups fit a CU at d = 128, four at d = 64: LDS and
     // registers); the work order was made for exactly this many workgroups
     const unsigned grid = 8u * (unsigned)fp.per_xcd;
@@ -1173,7 +1206,7 @@ static hipError_t launch_row(const smha_plan *plan, FwdParams &fp, hipStream_t s
 
 // Which grain of work items a call walks: the coarse lists unless they leave more than half of the
 // chip's workgroup slots empty for this batch and head count (then the longest list would be the launch).
-static int grain_for(const smha_plan *plan, int B, int H, int d) {
+static int grain_for(const smha_plan *plan, int B, int H, int d, int form) {
     if (!plan->fine_differs) return 0;
     int64_t n_items = 0;
     const WorkLists &w0 = plan->lists[0];
@@ -1182,33 +1215,47 @@ static int grain_for(const smha_plan *plan, int B, int H, int d) {
     else
         for (int bh = 0; bh < B * H; ++bh)
             n_items += w0.item_cnt[(plan->Bm > 1 ? bh / H : 0) * plan->Hm + (plan->Hm > 1 ? bh % H : 0)];
-    return 2 * n_items < (int64_t)(d == 64 ? 4 : 2) * plan->n_cu ? 1 : 0;
+    return 2 * n_items < (int64_t)workgroups_per_cu(form, d) * plan->n_cu ? 1 : 0;
 }
 
 // The work order and workspaces for a call shape: found, or made now (allocates and copies; nothing
 // that exists is freed or moved).  *ws receives the workspace for this call (null if the plan splits
 // no group).
-static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, int lvl,
+static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, int lvl, int form,
                                   const smha_plan::Prepared **out, void **ws, bool may_allocate = true) {
     std::lock_guard<std::mutex> lock(plan->prepared_mutex);
     smha_plan::Prepared *hit = nullptr;
     for (smha_plan::Prepared *q : plan->prepared)
-        if (q->B == B && q->H == H && q->d == d && q->lvl == lvl) hit = q;
+        if (q->B == B && q->H == H && q->d == d && q->lvl == lvl && q->form == form) hit = q;
     if (!hit && !may_allocate) return SMHA_ERR_UNSUPPORTED;
     if (!hit) {
         const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
         std::vector<int32_t> table;
         int per_xcd = 0;
-        const int slots = (d == 64 ? 4 : 2) * plan->n_cu / 8;  // workgroups that fit an XCD at once
+        const int slots = workgroups_per_cu(form, d) * plan->n_cu / 8;  // workgroups that fit an XCD at once
         smha_plan::Prepared *q = nullptr;
         try {
             build_work_order(plan, lvl, B, H, slots, table, per_xcd);
+            if (form == 2) {  // the second form reads a whole record per list position instead of following two indices
+                std::vector<int32_t> recs(16 + (table.size() - 16) / 2 * 8);
+                std::copy(table.begin(), table.begin() + 16, recs.begin());
+                for (size_t i = 0; i < (table.size() - 16) / 2; ++i) {
+                    const int32_t bh = table[16 + 2 * i];
+                    WorkRec r{-1, 0, 0, 0, 0, -1, -1, 0};
+                    if (bh >= 0) {
+                        const Item &it = wl.items[table[16 + 2 * i + 1]];
+                        r = WorkRec{bh / H, bh % H, it.qtile, it.begin, it.end - it.begin, it.slot, it.split, 0};
+                    }
+                    std::memcpy(&recs[16 + 8 * i], &r, sizeof r);
+                }
+                table.swap(recs);
+            }
             q = new smha_plan::Prepared();
         } catch (const std::bad_alloc &) {
             return SMHA_ERR_ALLOC;
         }
-        q->B = B; q->H = H; q->d = d; q->lvl = lvl; q->per_xcd = per_xcd;
+        q->B = B; q->H = H; q->d = d; q->lvl = lvl; q->form = form; q->per_xcd = per_xcd;
         for (int x = 0; x < 8; ++x) q->longest = std::max(q->longest, table[8 + x]);
         bool ok = hipMalloc((void **)&q->order, table.size() * sizeof(int32_t)) == hipSuccess &&
                   hipMemcpy(q->order, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
@@ -1261,9 +1308,14 @@ extern "C" smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H
         (void)hipGetLastError();
         return SMHA_ERR_HIP;
     }
-    const smha_plan::Prepared *pr = nullptr;
-    void *ws = nullptr;
-    return prepared_for(plan, B, H, d, grain_for(plan, B, H, d), &pr, &ws);
+    for (int bf16 = 0; bf16 < 2; ++bf16) {  // (the two input types may run different forms of the kernel)
+        const int form = block_form(plan, d, bf16 != 0);
+        const smha_plan::Prepared *pr = nullptr;
+        void *ws = nullptr;
+        const smha_status_t s2 = prepared_for(plan, B, H, d, grain_for(plan, B, H, d, form), form, &pr, &ws);
+        if (s2 != SMHA_OK) return s2;
+    }
+    return SMHA_OK;
 }
 
 // Workspace in the library's own image, for callers that cannot allocate: one array per GPU, kept
@@ -1343,7 +1395,8 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
-    const int lvl = grain_for(plan, B, H, d);
+    const int form = block_form(plan, d, in_dtype == SMHA_BF16);
+    const int lvl = grain_for(plan, B, H, d, form);
     const WorkLists &wl = plan->lists[lvl];
     fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl];
     fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
@@ -1357,7 +1410,8 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
         const smha_plan::Prepared *pr = nullptr;
         void *ws = nullptr;
-        const smha_status_t st = prepared_for(plan, B, H, d, lvl, &pr, &ws, !static_ws);
+        const smha_status_t st = prepared_for(plan, B, H, d, lvl, form, &pr, &ws, !static_ws);
+        fp.form = form;
         if (st != SMHA_OK) return st;
         if (static_ws && pr->ws_bytes) {
             // the library's own array instead of a workspace of the plan; its counters are cleared by a

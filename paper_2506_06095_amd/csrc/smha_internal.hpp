@@ -124,7 +124,7 @@ struct smha_plan {
     // the plan is destroyed: a launch that is still queued, or a captured graph, never loses them.
     static constexpr int kCallSlots = 4;
     struct Prepared {
-        int B = 0, H = 0, d = 0, lvl = 0, per_xcd = 0, longest = 0;
+        int B = 0, H = 0, d = 0, lvl = 0, form = 1, per_xcd = 0, longest = 0;  // form: which block kernel the order is for
         int32_t *order = nullptr;
         size_t ws_bytes = 0, counters_at = 0;  // one workspace; byte offset of its counters
         void *ws[kCallSlots] = {nullptr, nullptr, nullptr, nullptr};
