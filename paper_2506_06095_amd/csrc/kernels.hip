@@ -48,6 +48,10 @@ struct FwdParams {
     // positions r, r + gridDim.x / 8, ... until the list ends or a pair with batch*head < 0 comes up.
     // order_hdr = {start of each XCD's list (8), length (8)}
     const int32_t *order, *order_hdr;
+    // second form: order_hdr = per workgroup {first step, steps, first item, items}, order = StepRec
+    // records (step_bytes of them), order_items = ItemRec records (item_bytes)
+    const int32_t *order_items;
+    int64_t step_bytes, item_bytes;
     int form;    // 1: (batch*head, item) pairs in `order`; 2: WorkRec records
     int n_work;  // 8 * the longest list
     int per_xcd; // workgroups per XCD the order was made for (host side: the grid is 8 times this)
@@ -1232,31 +1236,66 @@ static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, in
         const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
         std::vector<int32_t> table;
-        int per_xcd = 0;
+        int per_xcd = 0, longest = 0;
+        int64_t step_words = 0, item_words = 0;
         const int slots = workgroups_per_cu(form, d) * plan->n_cu / 8;  // workgroups that fit an XCD at once
         smha_plan::Prepared *q = nullptr;
         try {
             build_work_order(plan, lvl, B, H, slots, table, per_xcd);
-            if (form == 2) {  // the second form reads a whole record per list position instead of following two indices
-                std::vector<int32_t> recs(16 + (table.size() - 16) / 2 * 8);
-                std::copy(table.begin(), table.begin() + 16, recs.begin());
-                for (size_t i = 0; i < (table.size() - 16) / 2; ++i) {
-                    const int32_t bh = table[16 + 2 * i];
-                    WorkRec r{-1, 0, 0, 0, 0, -1, -1, 0};
-                    if (bh >= 0) {
-                        const Item &it = wl.items[table[16 + 2 * i + 1]];
-                        r = WorkRec{bh / H, bh % H, it.qtile, it.begin, it.end - it.begin, it.slot, it.split, 0};
+            longest = 0;
+            for (int x = 0; x < 8; ++x) longest = std::max(longest, table[8 + x]);
+            if (form == 2) {
+                // The second form walks, per workgroup, one contiguous stream of steps and one of items
+                // (see StepRec / ItemRec): {8 offsets} + per workgroup {first step, steps, first item,
+                // items} + step records + item records.
+                const int n_wg = 8 * per_xcd;
+                std::vector<int32_t> hdr((size_t)4 * n_wg, 0), steps, items;
+                for (int wg = 0; wg < n_wg; ++wg) {
+                    const int x = wg & 7, r = wg >> 3;
+                    hdr[4 * wg] = (int32_t)(steps.size() / 4);
+                    hdr[4 * wg + 2] = (int32_t)(items.size() / 8);
+                    int n_it = 0;
+                    for (int pos = r; pos < table[8 + x]; pos += per_xcd) {
+                        const int32_t bh = table[16 + 2 * (table[x] + pos)];
+                        if (bh < 0) break;
+                        const Item &it = wl.items[table[16 + 2 * (table[x] + pos) + 1]];
+                        const int32_t rec[8] = {bh / H, bh % H, it.qtile, it.slot, it.split, 0, 0, 0};
+                        items.insert(items.end(), rec, rec + 8);
+                        const int n = it.end - it.begin;
+                        for (int e = 0; e < std::max(n, 1); ++e) {  // (an item without entries is one step that loads and computes nothing)
+                            const int32_t meta = n_it | (e == 0 ? kStepFirst : 0) | (e == std::max(n, 1) - 1 ? kStepLast : 0);
+                            const UEntry none{-1, {-2, -2}, 0};
+                            const UEntry &u = n > 0 ? plan->h_uent[it.begin + e] : none;
+                            const int32_t st[4] = {u.col, u.code[0], u.code[1], meta};
+                            steps.insert(steps.end(), st, st + 4);
+                        }
+                        ++n_it;
                     }
-                    std::memcpy(&recs[16 + 8 * i], &r, sizeof r);
+                    hdr[4 * wg + 1] = (int32_t)(steps.size() / 4) - hdr[4 * wg];
+                    hdr[4 * wg + 3] = n_it;
                 }
-                table.swap(recs);
+                if (items.size() / 8 > (size_t)kStepItemMask || steps.size() / 4 > (size_t)INT32_MAX / 16) return SMHA_ERR_UNSUPPORTED;
+                std::vector<int32_t> all(8, 0);
+                all[0] = 8;                                  // per-workgroup headers
+                all[1] = all[0] + (int32_t)hdr.size();       // step records
+                all[2] = all[1] + (int32_t)steps.size();     // item records
+                all[3] = all[2] + (int32_t)items.size();     // end
+                all.insert(all.end(), hdr.begin(), hdr.end());
+                all.insert(all.end(), steps.begin(), steps.end());
+                all.insert(all.end(), items.begin(), items.end());
+                all.resize(all.size() + 256, 0);             // (whole 1 KiB requests past the last record stay inside the buffer's bounds check anyway; slack for tidiness)
+                table.swap(all);
+                step_words = (int64_t)steps.size();
+                item_words = (int64_t)items.size();
             }
             q = new smha_plan::Prepared();
         } catch (const std::bad_alloc &) {
             return SMHA_ERR_ALLOC;
         }
         q->B = B; q->H = H; q->d = d; q->lvl = lvl; q->form = form; q->per_xcd = per_xcd;
-        for (int x = 0; x < 8; ++x) q->longest = std::max(q->longest, table[8 + x]);
+        q->longest = longest;
+        q->step_words = step_words;
+        q->item_words = item_words;
         bool ok = hipMalloc((void **)&q->order, table.size() * sizeof(int32_t)) == hipSuccess &&
                   hipMemcpy(q->order, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
         if (ok && wl.max_slots > 0) {
@@ -1426,6 +1465,13 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
         }
         fp.order_hdr = pr->order;
         fp.order = pr->order + 16;
+        if (form == 2) {
+            fp.order_hdr = pr->order + 8;
+            fp.order = pr->order + 8 + 4 * 8 * (int64_t)pr->per_xcd;
+            fp.order_items = fp.order + pr->step_words;
+            fp.step_bytes = pr->step_words * 4;
+            fp.item_bytes = pr->item_words * 4;
+        }
         fp.n_work = 8 * pr->longest;
         fp.per_xcd = pr->per_xcd;
         fp.scratch = (float *)ws;

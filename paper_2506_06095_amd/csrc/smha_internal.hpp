@@ -57,6 +57,14 @@ constexpr int kMaxGatherPerItem = 16;
 // of band masks but measured 5-15 % slower there: gathered tiles always take the bitmap path)
 constexpr int kGatherMaxCols = 16;
 
+// The second form of the block kernel reads, per workgroup, a contiguous stream of steps (one per
+// staged K/V tile, in execution order across the workgroup's items) and a contiguous stream of items.
+// StepRec = {key tile (-1: nothing to load), code for the group's first / second 64 rows (see UEntry),
+// meta}; meta = index of the step's item within the workgroup's items, plus kStepFirst / kStepLast on
+// an item's first / last step.  ItemRec = {batch, head, 128-row group, workspace slot or -1, split
+// group or -1, 0, 0, 0}.
+constexpr int32_t kStepFirst = 1 << 28, kStepLast = 1 << 29, kStepItemMask = (1 << 28) - 1;
+
 // A supertile whose list was split: `count` partials starting at scratch slot `slot0`.
 struct SplitRow {
     int32_t qtile, slot0, count, pad;
@@ -126,6 +134,7 @@ struct smha_plan {
     struct Prepared {
         int B = 0, H = 0, d = 0, lvl = 0, form = 1, per_xcd = 0, longest = 0;  // form: which block kernel the order is for
         int32_t *order = nullptr;
+        int64_t step_words = 0, item_words = 0;  // second form: sizes of the step and item streams inside `order`
         size_t ws_bytes = 0, counters_at = 0;  // one workspace; byte offset of its counters
         void *ws[kCallSlots] = {nullptr, nullptr, nullptr, nullptr};
         unsigned next = 0;
