@@ -224,24 +224,20 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
 // rows' running maximum in units of the exponent (-inf if none), l_tot their running sum.
 // The partial result goes to the workspace, register by register (64 consecutive floats per wave
 // instruction).  Parts run on any XCD and the XCDs' L2 caches are not coherent with each other, so these
-// stores and the loads below are device-scope atomic accesses (they go through to memory), and the wave
-// waits for its stores before it counts itself in: when the counter reads count - 1, every other part's
-// quarter is in memory.  The wave that finds it so merges all parts in list order (its own included,
-// re-read: the result does not depend on which part came last) and writes O.
-template <int D, int OUT>
-__device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
-                                                  int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
+// stores and the loads of the merge are device-scope atomic accesses (they go through to memory), and the
+// wave waits for its stores before it counts itself in: when the counter reads count - 1, every other
+// part's quarter is in memory.  The wave that finds it so owns the merge: it leaves its mark (its
+// workgroup's number) in the counter and merges when it sees fit (merge_split_parts).
+constexpr uint32_t kMergeMark = 0x80000000u;
+template <int D>
+__device__ __forceinline__ void put_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
+                                               int w, int lane, int b, int h, int bh, int slot, int split) {
     constexpr int NDT = D / 32;
     constexpr int NR = 16 * NDT;                     // accumulator registers per lane
     constexpr size_t SLOT = (size_t)(128 * D + 512);  // floats per workspace slot
-    const int hh = lane >> 5;
-    const float NEG_INF = -__builtin_inff();
     float *mine = p.scratch + ((size_t)bh * p.max_slots + slot) * SLOT;
     auto put = [&](float *ptr, float v) __attribute__((always_inline)) {
         __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
-    auto get = [&](const float *ptr) __attribute__((always_inline)) {
-        return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
@@ -251,13 +247,34 @@ __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x
     put(mine + 128 * D + 256 + w * 64 + lane, l_tot);
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0): the stores above have completed
     const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
-    const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + split);
+    const int count = uniform_load(&p.split_rows[uniform_load(p.split_off + mask) + split].count);
     uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
-    uint32_t seen = 0;
-    if (lane == 0) seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    seen = __builtin_amdgcn_readfirstlane(seen);
-    if ((int)seen != sr.count - 1) return;
-    if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // for the next launch
+    if (lane == 0) {
+        const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((int)seen == count - 1) __hip_atomic_store(counter, kMergeMark | blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// The merge of a split group's quarter w, by the wave that owns it (see put_split_part; any other wave
+// returns at once): all parts in list order (the owner's included, re-read: the result does not depend on
+// which part came last), then O; the counter goes back to zero for the next launch.
+template <int D, int OUT>
+__device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int lane, int b, int h, int bh, int qrow, int split) {
+    constexpr int NDT = D / 32;
+    constexpr int NR = 16 * NDT;
+    constexpr size_t SLOT = (size_t)(128 * D + 512);
+    const int hh = lane >> 5;
+    const float NEG_INF = -__builtin_inff();
+    auto get = [&](const float *ptr) __attribute__((always_inline)) {
+        return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
+    uint32_t state = 0;
+    if (lane == 0) state = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (__builtin_amdgcn_readfirstlane(state) != (kMergeMark | blockIdx.x)) return;
+    if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
+    const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + split);
     const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * SLOT;
     float mstar = NEG_INF;
     for (int c0 = 0; c0 < sr.count; c0 += 8) {  // (eight loads in flight at a time)
@@ -313,7 +330,17 @@ __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x
 
 // GATHER: the plan holds gathered tiles (staged rows that come from arbitrary key numbers, see
 // UEntry); plans without any run the instantiation that does not know about them.
-template <int D, bool BF16, int OUT, bool GATHER>
+template <int D, int OUT>
+__device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
+                                                  int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
+    put_split_part<D>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // (the mark, if this wave left one, is read back by merge_split_parts)
+    merge_split_parts<D, OUT>(p, w, lane, b, h, bh, qrow, split);
+}
+
+// SPLIT: the plan cuts some 128-row groups into parts (the instantiation for plans that do not carries
+// none of the merge code: its registers would be paid for in every item's start and end).
+template <int D, bool BF16, int OUT, bool GATHER, bool SPLIT>
 __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
@@ -765,12 +792,30 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                                     o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
             }
         } else {
-            finish_split_part<D, OUT>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh, qrow, item.slot, item.split);
+            if constexpr (SPLIT)
+                put_split_part<D>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh, item.slot, item.split);
         }
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     }
     item = nxt;
     }  // persistent loop over work items
+    if constexpr (SPLIT) {
+        // Second walk over this workgroup's items: the split groups whose last part one of its waves wrote
+        // are merged here, where nothing of the tile loop is alive any more (the merge needs many registers,
+        // and inside the loop every item's start and end would pay for them).
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        for (int pos2 = blockIdx.x >> 3; pos2 < list_len; pos2 += per_xcd) {
+            struct Pair { int32_t bh, index; };
+            const Pair pr = uniform_load(reinterpret_cast<const Pair *>(p.order) + list_at + pos2);
+            if (pr.bh < 0) break;
+            const Item *ip = p.items + pr.index;
+            const int slot = uniform_load(&ip->slot);
+            if (slot < 0) continue;
+            const int qtile = uniform_load(&ip->qtile), split = uniform_load(&ip->split);
+            const int b2 = pr.bh / p.H, h2 = pr.bh - b2 * p.H;
+            merge_split_parts<D, OUT>(p, w, lane, b2, h2, pr.bh, qtile * 128 + 32 * w + j, split);
+        }
+    }
 }
 
 #include "block_fwd2.inc"
@@ -1179,10 +1224,18 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     // the grid fills the chip once (two workgroups fit a CU at d = 128, four at d = 64: LDS and
     // registers); the work order was made for exactly this many workgroups
     const unsigned grid = 8u * (unsigned)fp.per_xcd;
-    if (plan->n_gathered > 0)
-        hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true>), dim3(grid), dim3(256), 0, stream, fp);
-    else
-        hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false>), dim3(grid), dim3(256), 0, stream, fp);
+    const bool split = fp.max_slots > 0;
+    if (plan->n_gathered > 0) {
+        if (split)
+            hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true, true>), dim3(grid), dim3(256), 0, stream, fp);
+        else
+            hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true, false>), dim3(grid), dim3(256), 0, stream, fp);
+    } else {
+        if (split)
+            hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false, true>), dim3(grid), dim3(256), 0, stream, fp);
+        else
+            hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, false, false>), dim3(grid), dim3(256), 0, stream, fp);
+    }
     return hipGetLastError();
 }
 
