@@ -63,6 +63,11 @@ typedef struct {
     int no_gather;  /* nonzero: the block kernel visits every non-empty 64x64 tile as it is; 0: tiles
                        with few used key columns are repacked into gathered tiles (block kernel
                        work lists only; the exported formats are never affected)               */
+    int block_form; /* which form of the block-wise kernel runs where both exist: 0 = the library's choice,
+                       1 = four waves per workgroup, every wave forms scores, probabilities and output of
+                       its rows (two to four workgroups per compute unit); 2 = eight waves per workgroup,
+                       score waves and value waves, one workgroup per compute unit.  Plans with gathered
+                       tiles, and bfloat16 at d = 128, always run form 1.  For measurements and tests.   */
 } smha_plan_opts_t;
 
 /* Mask description: the atomic patterns of the paper (Sec. 2.1.2, Fig. 1) and their

@@ -38,7 +38,7 @@ class SmhaError(RuntimeError):
 class PlanOpts(C.Structure):
     _fields_ = [("block", C.c_int), ("force", C.c_int), ("selector", C.c_int),
                 ("build_both", C.c_int), ("device_id", C.c_int), ("head_dim", C.c_int),
-                ("no_gather", C.c_int)]
+                ("no_gather", C.c_int), ("block_form", C.c_int)]
 
 
 class MaskDesc(C.Structure):
@@ -114,9 +114,9 @@ def smha_status_string(status: int) -> str:
 
 
 def _opts(block=0, force=SMHA_KERNEL_AUTO, selector=SMHA_SELECTOR_CALIBRATED, build_both=False,
-          device_id=-1, head_dim=0, no_gather=False) -> PlanOpts:
+          device_id=-1, head_dim=0, no_gather=False, block_form=0) -> PlanOpts:
     return PlanOpts(int(block), int(force), int(selector), int(bool(build_both)), int(device_id),
-                    int(head_dim), int(bool(no_gather)))
+                    int(head_dim), int(bool(no_gather)), int(block_form))
 
 
 def smha_plan_from_dense(mask, **opts) -> int:

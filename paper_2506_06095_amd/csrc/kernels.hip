@@ -1198,17 +1198,18 @@ using namespace smha;
 
 static bool strides_ok(const int64_t *s) { return !s || (s[0] % 8 == 0 && s[1] % 8 == 0 && s[2] % 8 == 0 && s[2] > 0); }
 
-// Which form of the block kernel runs a call: the second form (score and value waves, one workgroup per
-// compute unit) wherever it exists; plans with gathered tiles, and bfloat16 at d = 128 (its LDS does not
-// hold two probability operands per step), run the first.  SMHA_BLOCK_FORM=1 or 2 in the environment
-// (read once) overrides the choice where both exist.
+// Which form of the block kernel runs a call: the plan's block_form option, else SMHA_BLOCK_FORM=1 or 2 in
+// the environment (read once), else the first form (on the workloads measured so far it is the faster
+// one).  Plans with gathered tiles, and bfloat16 at d = 128 (the second form's LDS does not hold two
+// probability operands per step there), run the first form whatever is asked for.
 static int block_form(const smha_plan *plan, int d, bool bf16) {
-    static const int forced = [] {
+    static const int from_env = [] {
         const char *e = getenv("SMHA_BLOCK_FORM");
         return e ? atoi(e) : 0;
     }();
     if (plan->n_gathered > 0 || (bf16 && d == 128)) return 1;
-    return forced == 2 ? 2 : 1;
+    const int asked = plan->opts.block_form ? plan->opts.block_form : from_env;
+    return asked == 2 ? 2 : 1;
 }
 static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : 2); }
 

@@ -359,6 +359,7 @@ smha_status_t check_opts(const smha_plan_opts_t *in, smha_plan_opts_t &o) {
     if (o.selector != SMHA_SELECTOR_CALIBRATED && o.selector != SMHA_SELECTOR_PAPER_EQ1)
         return SMHA_ERR_INVALID_ARG;
     if (o.device_id < -2) return SMHA_ERR_INVALID_ARG;
+    if (o.block_form < 0 || o.block_form > 2) return SMHA_ERR_INVALID_ARG;
     if (o.head_dim == 0) o.head_dim = 64;
     if (o.head_dim != 64 && o.head_dim != 128) return SMHA_ERR_UNSUPPORTED;
     return SMHA_OK;
@@ -377,7 +378,7 @@ bool rows_wanted(const smha_plan_opts_t &o) { return o.build_both || o.force == 
 //               queries as keys; with Sq != Sk the ratio is taken over the nq * nk tiles of the
 //               mask and n in the logarithm is the key side, nk = ceil(Sk/16).
 //   calibrated: compare modelled times per (batch, head) pair:
-//               block = tiles64 * t_tile(d) ; row = nnz * t_entry(d) + Sq * t_rowfix
+//               block = steps * t_step(d) + t_fixed ; row = nnz * t_entry(d) + Sq * t_rowfix
 // ---------------------------------------------------------------------------------------
 static double eq1_threshold(double valid16, int Sq, int Sk) {
     const double nq = std::ceil(Sq / 16.0), nk = std::ceil(Sk / 16.0);
@@ -386,22 +387,27 @@ static double eq1_threshold(double valid16, int Sq, int Sk) {
     return valid16 / (nq * nk) - 1.2 / (lg * lg);
 }
 
-// Cost-model constants in nanoseconds of whole-chip time per (batch, head) pair, from MI355X
-// timings of both kernels with many pairs in flight:
-//   block kernel: 158 us / (32 pairs * 1249 tiles) = 4.0 ns per tile at d = 128 (BigBird, S 8192),
-//                 68 us / (64 pairs * 318 tiles) = 3.4 ns per tile at d = 64 (strided causal, S 2048);
-//   row kernel:   232 us / (64 pairs * 269376 entries) = 0.0134 ns per entry at d = 64,
-//                 3.24 ms / (32 pairs * 5.08 M entries) = 0.020 ns per entry at d = 128, and about
-//                 0.4 ns per query row of fixed cost (a wave per row); rows of at most 32 keys on
-//                 average share a wave four at a time, which cuts that to about a third (scattered
-//                 mask, 9 entries per row, 64 pairs: 68 us with a wave per row, 34-42 us shared).
+// Cost-model constants in nanoseconds of whole-chip time per (batch, head) pair, fitted to MI355X
+// timings of both kernels with 64 pairs in flight (sequence 512 / 2048 / 4096, scattered masks of 2 to
+// 64 random keys per row, sliding windows of 8 to 128, causal; least squares by hand on the 4096 rows):
+//   block kernel: time = steps * step_ns + fixed_ns, steps = staged K/V tiles of a pair (the union lists
+//                 of its 128-row groups) with a gathered tile counted as 1.5 (it takes the bitmap path
+//                 and gathers its rows).  d = 64: scattered 4096 4924 ns / 2048 steps = 2.4, causal 4096
+//                 3136 / 1056 = 3.0, scattered 2048 1330 / 512 = 2.6 -> 2.8; d = 128: 8400 / 2048 = 4.1,
+//                 4889 / 1056 = 4.6, BigBird 8192 (32 pairs) 125 us / 32 / 866 = 4.5 -> 4.5.  fixed_ns = 60:
+//                 what a launch of the block kernel costs beyond one of the row kernel, per pair at 64 pairs
+//                 (decides only the smallest masks: both kernels are launch-bound there);
+//   row kernel:   time = entries * entry_ns + rows * row_ns.  Rows of at most 32 keys on average share a wave
+//                 four at a time.  d = 64: entry 0.0096 (2 vs 16 keys per row: 568 ns / 57344 entries; 32 vs
+//                 64: 1134 / 129434 = 0.0088; causal 0.0100), row 0.13 shared / 0.44 with a wave per row;
+//                 d = 128: entry 0.0195 (0.0198, 0.0188, causal 0.0203), row 0.12 / 0.43.
+// Of the 60 measured cases the model now picks the slower kernel in 4, by at most 1.17x.
 struct CostModel {
-    double tile_ns, entry_ns, row_ns;
+    double step_ns, fixed_ns, entry_ns, row_ns;
 };
 static CostModel cost_model(int d, double mean_row_nnz) {
-    CostModel cm = d == 128 ? CostModel{4.0, 0.020, 0.5} : CostModel{3.4, 0.0134, 0.4};
-    if (mean_row_nnz <= 32.0) cm.row_ns /= 3.0;
-    return cm;
+    const bool shared = mean_row_nnz <= 32.0;
+    return d == 128 ? CostModel{4.5, 60.0, 0.0195, shared ? 0.12 : 0.43} : CostModel{2.8, 60.0, 0.0096, shared ? 0.13 : 0.44};
 }
 
 // Formats of one mask (64-wide tiles, no per-row lists) from what the GPU reported per tile.
@@ -451,7 +457,8 @@ static bool row_may_be_chosen(const smha_plan *p) {
     }
     if (p->opts.selector == SMHA_SELECTOR_PAPER_EQ1) return eq1_threshold(v16 / n_masks, p->S, p->Sk) < 0;
     const CostModel cm = cost_model(p->opts.head_dim, nnz / n_masks / p->S);
-    return nnz / n_masks * cm.entry_ns + p->S * cm.row_ns < tiles / n_masks * cm.tile_ns;
+    // (a pair's steps are at most its tiles: two tile rows share a staged tile, gathered tiles replace several)
+    return nnz / n_masks * cm.entry_ns + p->S * cm.row_ns < tiles / n_masks * cm.step_ns + cm.fixed_ns;
 }
 
 smha_status_t finish_plan(smha_plan *p) {
@@ -470,7 +477,6 @@ smha_status_t finish_plan(smha_plan *p) {
     const CostModel cm = cost_model(p->opts.head_dim, nnz / S);
     p->model_row_us = 1e-3 * (nnz * cm.entry_ns + S * cm.row_ns);
     p->row_mean_nnz = nnz / S;
-    int64_t n_replaced = 0;  // sparse tiles that gathered tiles stand in for
 
     try {
         // ---- block path first (its work lists say how many tiles the kernel will really visit,
@@ -534,7 +540,6 @@ smha_status_t finish_plan(smha_plan *p) {
                     } else {
                         keys.clear();
                         for (const Sparse &t : sparse) {
-                            n_replaced += (t.ea >= 0) + (t.eb >= 0);
                             for (uint64_t x = t.used; x; x &= x - 1) keys.push_back(t.col * 64 + __builtin_ctzll(x));
                         }
                         // keys ascend (tiles ascend, bits ascend); 64 per gathered tile
@@ -655,8 +660,9 @@ smha_status_t finish_plan(smha_plan *p) {
                 }
             }
         }
-        // a gathered tile serves both tile rows of its group: it counts as two tiles
-        p->model_block_us = 1e-3 * ((tiles + (2.0 * (double)p->n_gathered - (double)n_replaced) / n_masks) * cm.tile_ns);
+        // (no block lists were built: the forced row kernel; the estimate then falls back to one step per tile)
+        const double steps = p->h_uent.empty() ? tiles : ((double)p->h_uent.size() + 0.5 * (double)p->n_gathered) / n_masks;
+        p->model_block_us = 1e-3 * (steps * cm.step_ns + cm.fixed_ns);
         int choice;
         if (p->opts.force != SMHA_KERNEL_AUTO)
             choice = p->opts.force;

@@ -398,3 +398,11 @@ def test_selector_hand_values():
     assert selector.choose(1, 16) == "row" and selector.choose(1, 9) == "row"
     # dense mask at n = 2: 1 - 1.2/1 < 0 -> row-wise; at n = 4: 1 - 0.3 > 0 -> block
     assert selector.choose(4, 32) == "row" and selector.choose(16, 64) == "block"
+    # fewer queries than keys (this build's reading: ratio over the nq x nk tiles, n = nk in the logarithm), by hand:
+    # all ones, 64 queries x 512 keys: nq = 4, nk = 32, 128 tiles of 128 set, log2(32) = 5 -> 1 - 1.2/25
+    assert selector.valid16(np.ones((64, 512), dtype=np.uint8)) == 128
+    assert selector.threshold(128, 64, Sk=512) == pytest.approx(1.0 - 1.2 / 25.0, abs=1e-15)
+    # one key tile column set, 48 queries x 4096 keys: nq = 3, nk = 256, 3 tiles of 768 -> 1/256 - 1.2/64
+    assert selector.threshold(3, 48, Sk=4096) == pytest.approx(1.0 / 256.0 - 1.2 / 64.0, abs=1e-15)
+    # more queries than keys, 512 x 64: nq = 32, nk = 4, half of the tiles set -> 0.5 - 1.2/4
+    assert selector.threshold(64, 512, Sk=64) == pytest.approx(0.5 - 0.3, abs=1e-15)
