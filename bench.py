@@ -44,6 +44,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = BigBird, seq 8192)")
     ap.add_argument("--kernel", choices=["auto", "row", "block"], default="auto")
+    ap.add_argument("--scattered", type=int, default=0, metavar="K",
+                    help="instead of --config: a scattered mask (K pseudo-random keys per query plus the diagonal), batch 4, "
+                         "16 heads, sequence 2048, head size 64, fp16 -- the ground on which the selector takes the "
+                         "row-wise kernel (not one of the five configurations; for its roofline line and profile)")
     ap.add_argument("--prewarm-ms", type=float, default=80.0,
                     help="untimed forwards for this long before the W warm-up steps: the chip's clocks take "
                          "about 30 ms of load to settle (step time falls 20 %% over the first 200 steps)")
@@ -74,6 +78,10 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     c = W.config(args.config)
+    scattered = None
+    if args.scattered > 0:
+        c = W.scaled(W.config(3), name="scattered_2048_k%d" % args.scattered, seed=31, mask=None)
+        scattered = W.scattered_spec(c.S, args.scattered, 3)     # dense [1][1][S][S]
     B, H, S, d = c.B, c.H, c.S, c.d
     Q, K, V = W.qkv_bits(B, H, S, d, c.dtype, c.std, c.seed)
     tdt = torch.float16 if c.dtype == "f16" else torch.bfloat16
@@ -86,7 +94,11 @@ def main() -> int:
             sets.append(tuple(t.clone() for t in (q, k, v, out)))
 
     force = {"auto": smha.SMHA_KERNEL_AUTO, "row": smha.SMHA_KERNEL_ROW, "block": smha.SMHA_KERNEL_BLOCK}[args.kernel]
-    if args.dense_device_mask:
+    if scattered is not None:
+        t0 = time.perf_counter()
+        plan = smha.Plan.from_dense(scattered, block=c.block, head_dim=d, force=force)
+        plan_ms = (time.perf_counter() - t0) * 1e3
+    elif args.dense_device_mask:
         dense = W.dense_mask(c.mask, B, H, S)
         dev_mask = torch.from_numpy(dense).cuda()
         smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force).close()   # warm-up (first launch)
@@ -104,6 +116,10 @@ def main() -> int:
     pairs_per_mask = B * H // n_masks
     nnz_flops = 4.0 * info["nnz"] * pairs_per_mask * d
     tile_flops = 4.0 * info["n_tiles64"] * 64 * 64 * pairs_per_mask * d
+    if info["n_gathered"] > 0:
+        # gathered tiles stand in for many sparse tiles: the kernel then executes at most two tiles' worth of
+        # MFMA work per staged tile (one per 64-row half of a group), which is what the roofline may count
+        tile_flops = min(tile_flops, 2.0 * 4.0 * info["n_union"] * 64 * 64 * pairs_per_mask * d)
     kernel = "row" if info["kernel"] == smha.SMHA_KERNEL_ROW else "block"
 
     stream = torch.cuda.current_stream()
@@ -171,7 +187,9 @@ def main() -> int:
     tr = MEASURED_TRAFFIC.get((c.name, kernel))
     if tr is not None:
         roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
-        roof["traffic_detail"] = dict(tr, unit="bytes per launch", source="rocprofv3 --pmc, see profiles/")
+        roof["traffic_detail"] = dict(tr, unit="bytes per launch",
+                                      source="constants in bench.py, copied from the rocprofv3 --pmc summaries under profiles/ "
+                                             "(not measured by this run)")
     result = {
         "metric": "masked-MHA effective TFLOP/s over unmasked entries (latency in ms_per_step)",
         "value": nnz_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
@@ -183,7 +201,8 @@ def main() -> int:
                    "tiles64_per_step": info["n_tiles64"] * pairs_per_mask,
                    "kernel_steps_per_step": info["n_union"] * pairs_per_mask,
                    "gathered_tiles_per_step": info["n_gathered"] * pairs_per_mask,
-                   "plan_from": "dense device mask" if args.dense_device_mask else "pattern description",
+                   "plan_from": "dense host mask" if scattered is not None else
+                                "dense device mask" if args.dense_device_mask else "pattern description",
                    "cache": "cold (%d rotating sets)" % len(sets) if args.cold else "hot"},
         "latency_ms": {"timed_region_mean": launch_ms, "single_launch_mean": float(per.mean()),
                        "single_launch_median": float(np.median(per)), "single_launch_min": float(per.min())},
@@ -223,7 +242,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         import oracle
-        masks = W.dense_mask(c.mask, B, H, S)
+        masks = scattered if scattered is not None else W.dense_mask(c.mask, B, H, S)
         Bm, Hm = masks.shape[:2]
         flat = [(b, h) for b in range(B) for h in range(H)]
         n_heads = args.cpu_heads or max(1, min(len(flat), int(round(1.0e12 / (nnz_flops / len(flat))))))

@@ -258,7 +258,7 @@ __device__ __forceinline__ void put_split_part(const FwdParams &p, const f32x16 
 // The merge of a split group's quarter w, by the wave that owns it (see put_split_part; any other wave
 // returns at once): all parts in list order (the owner's included, re-read: the result does not depend on
 // which part came last), then O; the counter goes back to zero for the next launch.
-template <int D, int OUT>
+template <int D, int OUT, int PB, int RB>  // a batch of loads in flight: PB parts x RB accumulator registers
 __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int lane, int b, int h, int bh, int qrow, int split) {
     constexpr int NDT = D / 32;
     constexpr int NR = 16 * NDT;
@@ -289,7 +289,8 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
     for (int r = 0; r < NR; ++r) acc[r] = 0.f;
     float L = 0.f;
     if (mstar != NEG_INF) {
-        constexpr int PB = 4;  // parts per batch: their loads are in flight together
+        // (the merge runs where few registers are alive: many loads are in flight together, each batch costs
+        // one trip to memory)
         const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
         for (int c0 = 0; c0 < sr.count; c0 += PB) {
             float wgt[PB];
@@ -303,16 +304,16 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
                 L += wgt[u] * get(base + at[u] + 128 * D + 256 + w * 64 + lane);
             }
 #pragma unroll
-            for (int r0 = 0; r0 < NR; r0 += 8) {
-                float v[PB][8];
+            for (int r0 = 0; r0 < NR; r0 += RB) {
+                float v[PB][RB];
 #pragma unroll
                 for (int u = 0; u < PB; ++u)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
+                    for (int i = 0; i < RB; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
 #pragma unroll
                 for (int u = 0; u < PB; ++u)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
+                    for (int i = 0; i < RB; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
             }
         }
     }
@@ -335,7 +336,7 @@ __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x
                                                   int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
     put_split_part<D>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split);
     __builtin_amdgcn_s_waitcnt(0x0070);  // (the mark, if this wave left one, is read back by merge_split_parts)
-    merge_split_parts<D, OUT>(p, w, lane, b, h, bh, qrow, split);
+    merge_split_parts<D, OUT, 4, 8>(p, w, lane, b, h, bh, qrow, split);
 }
 
 // SPLIT: the plan cuts some 128-row groups into parts (the instantiation for plans that do not carries
@@ -813,7 +814,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             if (slot < 0) continue;
             const int qtile = uniform_load(&ip->qtile), split = uniform_load(&ip->split);
             const int b2 = pr.bh / p.H, h2 = pr.bh - b2 * p.H;
-            merge_split_parts<D, OUT>(p, w, lane, b2, h2, pr.bh, qtile * 128 + 32 * w + j, split);
+            merge_split_parts<D, OUT, 8, (D == 128 ? 16 : 4)>(p, w, lane, b2, h2, pr.bh, qtile * 128 + 32 * w + j, split);
         }
     }
 }
@@ -1265,7 +1266,7 @@ static hipError_t launch_row(const smha_plan *plan, FwdParams &fp, hipStream_t s
 // Which grain of work items a call walks: the coarse lists unless they leave more than half of the
 // chip's workgroup slots empty for this batch and head count (then the longest list would be the launch).
 static int grain_for(const smha_plan *plan, int B, int H, int d, int form) {
-    if (!plan->fine_differs) return 0;
+    if (!plan->fine_differs || !plan->has_block) return 0;
     int64_t n_items = 0;
     const WorkLists &w0 = plan->lists[0];
     if (plan->Bm == 1 && plan->Hm == 1)

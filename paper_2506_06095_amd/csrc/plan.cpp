@@ -685,6 +685,7 @@ smha_status_t finish_plan(smha_plan *p) {
             p->lists[0] = WorkLists{};
             p->lists[1] = WorkLists{};
             p->n_gathered = 0;
+            p->fine_differs = false;
         }
         // ---- row path: concatenate -------------------------------------------------
         if (p->has_row) {

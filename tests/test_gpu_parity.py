@@ -703,3 +703,18 @@ def test_second_form_ragged_and_split(torch_mod, smha, S, d, dtype):
         assert np.all(got[:, 1, S // 2] == 0.0) and np.all(got[:, 2, S // 3:] == 0.0)
         if dtype == "f16":
             run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, plan=plan, what=f"form 2 ragged {S} f16 out")
+
+
+def test_plan_that_holds_only_the_row_format(torch_mod, smha):
+    """A scattered mask without build_both: the selector takes the row-wise kernel and the plan keeps no block
+    lists at all; forward runs (and forcing the block kernel is refused)."""
+    S, d = 2048, 64
+    m = W.scattered_spec(S, 8, 3)
+    Q, K, V = W.qkv_bits(2, 4, S, d, "f16", 1.0, 77)
+    with smha.Plan.from_dense(m, head_dim=d) as plan:
+        info = plan.info()
+        assert info["kernel"] == smha.SMHA_KERNEL_ROW and not info["has_block_kernel_lists"]
+        run_case(torch_mod, smha, Q, K, V, "f16", m, 0, heads=[(0, 0), (1, 3)], plan=plan, what="row-only plan")
+        q = to_dev(torch_mod, Q, "f16")
+        with pytest.raises(smha.SmhaError):
+            plan.forward(q, q, q, kernel=smha.SMHA_KERNEL_BLOCK)
