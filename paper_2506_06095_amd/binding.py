@@ -247,6 +247,14 @@ def _strides3(t):
 _DTYPE_CODES = None
 
 
+def _current_raw_stream(torch, device) -> int:
+    """The handle of torch's current stream on `device` (the short way when torch offers it)."""
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    if raw is not None and device.index is not None:
+        return raw(device.index)
+    return torch.cuda.current_stream(device).cuda_stream
+
+
 def smha_forward_static(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_KERNEL_AUTO,
                         stream=None, _dims=None) -> None:
     """smha_forward through the entry point that allocates nothing (the shape must be prepared)."""
@@ -283,8 +291,9 @@ def smha_forward(plan: int, Q, K, V, O, scale: float = 0.0, kernel: int = SMHA_K
     if not (Q.is_cuda and K.is_cuda and V.is_cuda and O.is_cuda):
         raise ValueError("tensors must be on the GPU")
     if stream is None:
-        stream = torch.cuda.current_stream(Q.device)
-    handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+        handle = _current_raw_stream(torch, Q.device)
+    else:
+        handle = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
     st = getattr(lib, _entry)(plan, Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, d,
                               in_code, out_code, _strides3(Q), _strides3(K), _strides3(V), _strides3(O),
                               float(scale), int(kernel), handle)

@@ -230,7 +230,7 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
 // workgroup's number) in the counter and merges when it sees fit (merge_split_parts).
 constexpr uint32_t kMergeMark = 0x80000000u;
 template <int D>
-__device__ __forceinline__ void put_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
+__device__ __forceinline__ bool put_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
                                                int w, int lane, int b, int h, int bh, int slot, int split) {
     constexpr int NDT = D / 32;
     constexpr int NR = 16 * NDT;                     // accumulator registers per lane
@@ -249,17 +249,22 @@ __device__ __forceinline__ void put_split_part(const FwdParams &p, const f32x16 
     const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
     const int count = uniform_load(&p.split_rows[uniform_load(p.split_off + mask) + split].count);
     uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
+    int last = 0;
     if (lane == 0) {
         const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((int)seen == count - 1) __hip_atomic_store(counter, kMergeMark | blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = (int)seen == count - 1;
+        if (last) __hip_atomic_store(counter, kMergeMark | blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    return __builtin_amdgcn_readfirstlane(last) != 0;  // this wave owns the merge of its quarter
 }
 
 // The merge of a split group's quarter w, by the wave that owns it (see put_split_part; any other wave
 // returns at once): all parts in list order (the owner's included, re-read: the result does not depend on
 // which part came last), then O; the counter goes back to zero for the next launch.
+// (owner_known: the caller remembers put_split_part's answer, and the counter need not be asked)
 template <int D, int OUT, int PB, int RB>  // a batch of loads in flight: PB parts x RB accumulator registers
-__device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int lane, int b, int h, int bh, int qrow, int split) {
+__device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int lane, int b, int h, int bh, int qrow, int split,
+                                                  bool owner_known = false) {
     constexpr int NDT = D / 32;
     constexpr int NR = 16 * NDT;
     constexpr size_t SLOT = (size_t)(128 * D + 512);
@@ -269,63 +274,72 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
         return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
-    uint32_t state = 0;
-    if (lane == 0) state = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (__builtin_amdgcn_readfirstlane(state) != (kMergeMark | blockIdx.x)) return;
+    if (!owner_known) {
+        uint32_t state = 0;
+        if (lane == 0) state = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__builtin_amdgcn_readfirstlane(state) != (kMergeMark | blockIdx.x)) return;
+    }
     if (lane == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
     const SplitRow sr = uniform_load(p.split_rows + uniform_load(p.split_off + mask) + split);
     const float *base = p.scratch + ((size_t)bh * p.max_slots + sr.slot0) * SLOT;
+    // Every batch of loads costs one trip to memory, so as much as the registers hold travels together:
+    // RB accumulator registers of PB parts, with those parts' references (and, in the first batch, their
+    // sums); RB registers are finished and stored before the next RB are begun.  A group of at most PB
+    // parts finds its common reference in the first batch; longer ones take a pass over all references first.
+    const bool one_block = sr.count <= PB;
     float mstar = NEG_INF;
-    for (int c0 = 0; c0 < sr.count; c0 += 8) {  // (eight loads in flight at a time)
-        float ms[8];
+    if (!one_block) {
+        for (int c0 = 0; c0 < sr.count; c0 += 8) {
+            float ms[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) ms[u] = get(base + (size_t)min(c0 + u, sr.count - 1) * SLOT + 128 * D + w * 64 + lane);
+            for (int u = 0; u < 8; ++u) ms[u] = get(base + (size_t)min(c0 + u, sr.count - 1) * SLOT + 128 * D + w * 64 + lane);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mstar = fmaxf(mstar, ms[u]);
+            for (int u = 0; u < 8; ++u) mstar = fmaxf(mstar, ms[u]);
+        }
     }
-    float acc[NR];
+    const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
+    const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+    float L = 0.f, inv = 0.f;
 #pragma unroll
-    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-    float L = 0.f;
-    if (mstar != NEG_INF) {
-        // (the merge runs where few registers are alive: many loads are in flight together, each batch costs
-        // one trip to memory)
-        const float *mine_q = base + (size_t)w * NR * 64 + lane;  // this wave's quarter of part 0
+    for (int r0 = 0; r0 < NR; r0 += RB) {
+        float acc[RB];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) acc[i] = 0.f;
         for (int c0 = 0; c0 < sr.count; c0 += PB) {
-            float wgt[PB];
+            float mu[PB], lu[PB], v[PB][RB];
             int at[PB];  // float offset of part c0 + u from part 0 (parts past the end: part c0 again, weight 0)
 #pragma unroll
             for (int u = 0; u < PB; ++u) {
-                const bool live = c0 + u < sr.count;
-                at[u] = (live ? c0 + u : c0) * (int)SLOT;
-                const float mu = get(base + at[u] + 128 * D + w * 64 + lane);
-                wgt[u] = live ? fast_exp2(mu - mstar) : 0.f;  // (-inf - finite: 0)
-                L += wgt[u] * get(base + at[u] + 128 * D + 256 + w * 64 + lane);
+                at[u] = (c0 + u < sr.count ? c0 + u : c0) * (int)SLOT;
+                mu[u] = get(base + at[u] + 128 * D + w * 64 + lane);
+                if (r0 == 0) lu[u] = get(base + at[u] + 128 * D + 256 + w * 64 + lane);
             }
 #pragma unroll
-            for (int r0 = 0; r0 < NR; r0 += RB) {
-                float v[PB][RB];
+            for (int u = 0; u < PB; ++u)
 #pragma unroll
-                for (int u = 0; u < PB; ++u)
+                for (int i = 0; i < RB; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
+            if (r0 == 0 && one_block) {
 #pragma unroll
-                    for (int i = 0; i < RB; ++i) v[u][i] = get(mine_q + at[u] + (r0 + i) * 64);
+                for (int u = 0; u < PB; ++u) mstar = fmaxf(mstar, mu[u]);  // (parts past the end repeat part c0)
+            }
 #pragma unroll
-                for (int u = 0; u < PB; ++u)
+            for (int u = 0; u < PB; ++u) {
+                // (a row with no key in any part has -inf everywhere: weight 0, never -inf - -inf)
+                const float wgt = (c0 + u < sr.count && mu[u] != NEG_INF) ? fast_exp2(mu[u] - mstar) : 0.f;
+                if (r0 == 0) L += wgt * lu[u];
 #pragma unroll
-                    for (int i = 0; i < RB; ++i) acc[r0 + i] = fmaf(wgt[u], v[u][i], acc[r0 + i]);
+                for (int i = 0; i < RB; ++i) acc[i] = fmaf(wgt, v[u][i], acc[i]);
             }
         }
-    }
-    if (qrow < p.S) {
-        const float inv = L > 0.f ? 1.0f / L : 0.f;
-        const int64_t obase = b * p.os.b + h * p.os.h + (int64_t)qrow * p.os.s;
+        if (r0 == 0) inv = L > 0.f ? 1.0f / L : 0.f;
+        if (qrow < p.S) {
 #pragma unroll
-        for (int dt = 0; dt < NDT; ++dt)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4)
-                store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[16 * dt + 4 * g4] * inv, acc[16 * dt + 4 * g4 + 1] * inv,
-                            acc[16 * dt + 4 * g4 + 2] * inv, acc[16 * dt + 4 * g4 + 3] * inv);
+            for (int i = 0; i < RB; i += 4) {
+                const int r = r0 + i, dt = r >> 4, g4 = (r & 15) >> 2;
+                store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
+            }
+        }
     }
 }
 
@@ -334,9 +348,8 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
 template <int D, int OUT>
 __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
                                                   int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
-    put_split_part<D>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split);
-    __builtin_amdgcn_s_waitcnt(0x0070);  // (the mark, if this wave left one, is read back by merge_split_parts)
-    merge_split_parts<D, OUT, 4, 8>(p, w, lane, b, h, bh, qrow, split);
+    if (put_split_part<D>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split))
+        merge_split_parts<D, OUT, 4, 8>(p, w, lane, b, h, bh, qrow, split, true);
 }
 
 // SPLIT: the plan cuts some 128-row groups into parts (the instantiation for plans that do not carries
@@ -517,6 +530,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // Invariant at the top of the loop: everything requested for the item has landed (each way
     // into the loop ends with the wait that makes it so, which lets the compiler see it too).
     int pos = blockIdx.x >> 3;
+    int turn = 0;        // how many items this workgroup has taken
+    uint64_t owned = 0;  // wave-uniform: see put_split_part
     Work item = fetch_work(pos);
     if (item.valid) start_work(item);
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
@@ -793,28 +808,42 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                                     o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
             }
         } else {
-            if constexpr (SPLIT)
-                put_split_part<D>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh, item.slot, item.split);
+            if constexpr (SPLIT) {
+                // (which of its items' groups this wave has to merge is kept as one bit per turn; from turn 63
+                // on the bit only says that the counters of those turns have to be asked)
+                const bool last = put_split_part<D>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh,
+                                                    item.slot, item.split);
+                if (last || turn >= 63) owned |= 1ull << min(turn, 63);
+            }
         }
         __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
     }
     item = nxt;
+    ++turn;
     }  // persistent loop over work items
     if constexpr (SPLIT) {
         // Second walk over this workgroup's items: the split groups whose last part one of its waves wrote
         // are merged here, where nothing of the tile loop is alive any more (the merge needs many registers,
         // and inside the loop every item's start and end would pay for them).
         __builtin_amdgcn_s_waitcnt(0x0070);
-        for (int pos2 = blockIdx.x >> 3; pos2 < list_len; pos2 += per_xcd) {
+        auto merge_at = [&](int pos2, bool owner_known) __attribute__((always_inline)) {
             struct Pair { int32_t bh, index; };
             const Pair pr = uniform_load(reinterpret_cast<const Pair *>(p.order) + list_at + pos2);
-            if (pr.bh < 0) break;
+            if (pr.bh < 0) return;
             const Item *ip = p.items + pr.index;
-            const int slot = uniform_load(&ip->slot);
-            if (slot < 0) continue;
+            if (uniform_load(&ip->slot) < 0) return;
             const int qtile = uniform_load(&ip->qtile), split = uniform_load(&ip->split);
             const int b2 = pr.bh / p.H, h2 = pr.bh - b2 * p.H;
-            merge_split_parts<D, OUT, 8, (D == 128 ? 16 : 4)>(p, w, lane, b2, h2, pr.bh, qtile * 128 + 32 * w + j, split);
+            merge_split_parts<D, OUT, (D == 128 ? 8 : 4), 16>(p, w, lane, b2, h2, pr.bh, qtile * 128 + 32 * w + j, split, owner_known);
+        };
+        while (owned) {
+            const int k = __builtin_ctzll(owned);
+            owned &= owned - 1;
+            if (k < 63) {
+                merge_at((blockIdx.x >> 3) + k * per_xcd, true);
+            } else {
+                for (int pos2 = (blockIdx.x >> 3) + 63 * per_xcd; pos2 < list_len; pos2 += per_xcd) merge_at(pos2, false);
+            }
         }
     }
 }
