@@ -38,6 +38,7 @@ struct FwdParams {
     void *O;
     Strides qs, ks, vs, os;
     int B, H, S, Sk, Bm, Hm;  // S queries, Sk keys
+    int d;          // head size in memory: a multiple of 8, at most the kernel's D (columns d .. D-1 are read as zeros and never stored)
     int out_dtype;  // smha_dtype_t
     float c;        // scale * log2(e)
     // block path
@@ -337,7 +338,8 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
 #pragma unroll
             for (int i = 0; i < RB; i += 4) {
                 const int r = r0 + i, dt = r >> 4, g4 = (r & 15) >> 2;
-                store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
+                if (32 * dt + 8 * g4 + 4 * hh < p.d)
+                    store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
             }
         }
     }
@@ -445,16 +447,23 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // receives global chunk pc ^ swz(row).  Block w + 4 i starts 64 i / CPR * 4 rows (a multiple
     // of 16) below block w, which leaves the swizzle alone: one per-lane offset serves all i.
     constexpr int RSTEP = 4 * 64 / CPR;  // rows between two of a wave's blocks
-    int k_go, v_go;
+    // A head narrower than D has no chunks d/8 .. CPR-1: a lane whose chunk is one of them carries kNoChunk
+    // instead of its offset.  Offsets are unsigned 32-bit sums below 2^31 (the host checks the sizes), so with
+    // kNoChunk added they stay past every buffer, the load returns zeros and a store is dropped.
+    constexpr uint32_t kNoChunk = 0x80000000u;
+    const int cpr_d = p.d >> 3;  // chunks a row has in memory
+    uint32_t k_go, v_go;
     {
         const int pchunk = w * 64 + lane;
         const int row = pchunk / CPR, pc = pchunk % CPR;
-        k_go = row * ksb + (pc ^ swz_k<D>(row)) * 16;
-        v_go = row * vsb + (pc ^ swz_v<D>(row)) * 16;
+        const int kc = pc ^ swz_k<D>(row), vc = pc ^ swz_v<D>(row);
+        k_go = kc < cpr_d ? (uint32_t)(row * ksb + kc * 16) : kNoChunk;
+        v_go = vc < cpr_d ? (uint32_t)(row * vsb + vc * 16) : kNoChunk;
     }
     // With gathered tiles a staged row may come from any key: offset = key * pitch + chunk part.
     const int g_row = (w * 64 + lane) / CPR;  // the lane's row in the wave's first block
-    const int g_kc = k_go - g_row * ksb, g_vc = v_go - g_row * vsb;
+    const uint32_t g_kc = k_go == kNoChunk ? kNoChunk : k_go - (uint32_t)(g_row * ksb);
+    const uint32_t g_vc = v_go == kNoChunk ? kNoChunk : v_go - (uint32_t)(g_row * vsb);
     const uint32_t gix_lds = (uint32_t)(uintptr_t)(lds_void *)gix;
 
     // state of the item being started / computed
@@ -471,9 +480,9 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     constexpr int NQL = CPR / 2;  // 1 KiB pieces of a 32-row slab
     // Request everything an item needs before its first tile can be computed.
     auto start_work = [&](const Work &wk) __attribute__((always_inline)) {
-        const u32x4 rQ = make_rsrc4(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + D) * 2);
-        rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(p.Sk - 1) * p.ks.s + D) * 2);
-        rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(p.Sk - 1) * p.vs.s + D) * 2);
+        const u32x4 rQ = make_rsrc4(p.Q + wk.b * p.qs.b + wk.h * p.qs.h, ((int64_t)(S - 1) * p.qs.s + p.d) * 2);
+        rK = make_rsrc4(p.K + wk.b * p.ks.b + wk.h * p.ks.h, ((int64_t)(p.Sk - 1) * p.ks.s + p.d) * 2);
+        rV = make_rsrc4(p.V + wk.b * p.vs.b + wk.h * p.vs.h, ((int64_t)(p.Sk - 1) * p.vs.s + p.d) * 2);
         {
             // (one 16-byte request per lane: every memory instruction here holds the wave ~100 cycles)
             typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
@@ -496,7 +505,8 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         for (int i = 0; i < NQL; ++i) {
             const int pchunk = i * 64 + lane_o;
             const int row = pchunk / CPR, pc = pchunk % CPR;
-            load_to_lds(rQ, priv_lds + i * 1024, (q0 + row) * (int)p.qs.s * 2 + (pc ^ swz_k<D>(row)) * 16);
+            const int qc = pc ^ swz_k<D>(row);
+            load_to_lds(rQ, priv_lds + i * 1024, qc < cpr_d ? (q0 + row) * (int)p.qs.s * 2 + qc * 16 : (int)kNoChunk);
         }
         if constexpr (GATHER) {
             // the key numbers of the item's gathered tiles -> LDS; wave w brings blocks 4 w .. 4 w + 3
@@ -781,14 +791,15 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
         // NQL stores, every one issued by every wave (rows past S fall outside the buffer and are
         // dropped), so that the wait below can count them
         const __amdgpu_buffer_rsrc_t rO = make_rsrc(reinterpret_cast<const uint16_t *>(p.O) + b * p.os.b + h * p.os.h,
-                                                    ((int64_t)(S - 1) * p.os.s + D) * 2);
+                                                    ((int64_t)(S - 1) * p.os.s + p.d) * 2);
 #pragma unroll
         for (int i = 0; i < NQL; ++i) {
             const int pchunk = i * 64 + lane_e;
             const int row = pchunk / CPR, pc = pchunk % CPR;
+            const int oc = pc ^ swz_k<D>(row);
             // (aux 2 = streaming: O is not read again here, and lines kept for it would push K and V out of the
             // XCD's L2: measured 144 -> 134 us on the 8k BigBird workload)
-            __builtin_amdgcn_raw_buffer_store_b128(ov[i], rO, (q0 + row) * (int)p.os.s * 2 + (pc ^ swz_k<D>(row)) * 16, 0, 2);
+            __builtin_amdgcn_raw_buffer_store_b128(ov[i], rO, oc < cpr_d ? (q0 + row) * (int)p.os.s * 2 + oc * 16 : (int)kNoChunk, 0, 2);
         }
         // The next item's requests were issued before these stores and memory operations retire
         // in order: allowing NQL operations to stay outstanding waits for the requests only.
@@ -804,8 +815,9 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                 for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
                     for (int g4 = 0; g4 < 4; ++g4)
-                        store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
-                                    o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
+                        if (32 * dt + 8 * g4 + 4 * hh < p.d)
+                            store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, o[dt][4 * g4] * inv, o[dt][4 * g4 + 1] * inv,
+                                        o[dt][4 * g4 + 2] * inv, o[dt][4 * g4 + 3] * inv);
             }
         } else {
             if constexpr (SPLIT) {
@@ -889,16 +901,20 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
     if ((rb * 4 + wave) * RPW >= p.S) return;  // (whole waves leave together)
     const bool row_ok = i_raw < p.S;           // rows past the end stay for the shuffles below, with no keys
     const int i = row_ok ? i_raw : p.S - 1;
-    const int sub = lane % LPK, g = (lane % LPR) / LPK;
+    const int sub_raw = lane % LPK, g = (lane % LPR) / LPK;
+    // a head narrower than D: the lanes past its last column read column 0 again, with a zero query, and store nothing
+    const bool col_ok = 8 * sub_raw < p.d;
+    const int sub = col_ok ? sub_raw : 0;
     const float NEG_INF = -__builtin_inff();
 
     float qf[8];
     {
         u32x4 v = *reinterpret_cast<const u32x4 *>(p.Q + b * p.qs.b + h * p.qs.h + (int64_t)i * p.qs.s + 8 * sub);
+        const float cq = col_ok ? p.c : 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            qf[2 * e] = widen16<BF16>(v[e] & 0xFFFFu) * p.c;
-            qf[2 * e + 1] = widen16<BF16>(v[e] >> 16) * p.c;
+            qf[2 * e] = widen16<BF16>(v[e] & 0xFFFFu) * cq;
+            qf[2 * e + 1] = widen16<BF16>(v[e] >> 16) * cq;
         }
     }
     const int32_t *rp = p.row_ptr + (size_t)mask * (p.S + 1);
@@ -967,7 +983,7 @@ __global__ void __launch_bounds__(256) smha_row_fwd(const FwdParams p) {
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] * wa + __shfl_xor(acc[e], off) * wb;
         m = m_new;
     }
-    if (g == 0 && row_ok) {
+    if (g == 0 && row_ok && col_ok) {
         const float inv = l > 0.f ? 1.0f / l : 0.f;
         const int64_t o = b * p.os.b + h * p.os.h + (int64_t)i * p.os.s + 8 * sub;
         store_out4(p.O, o, p.out_dtype, acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
@@ -1413,9 +1429,14 @@ static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, in
     return SMHA_OK;
 }
 
+// Head sizes: any multiple of 8 up to 128.  The kernels exist for 64 and 128 columns; a narrower head
+// runs on the next of the two, its missing columns read as zeros (which changes no score) and never stored.
+static bool head_size_ok(int d) { return d >= 8 && d <= 128 && d % 8 == 0; }
+static int kernel_head_size(int d) { return d <= 64 ? 64 : 128; }
+
 static smha_status_t check_shape(const smha_plan *plan, int B, int H, int d) {
     if (!plan || B < 1 || H < 1) return SMHA_ERR_INVALID_ARG;
-    if (d != 64 && d != 128) return SMHA_ERR_UNSUPPORTED;
+    if (!head_size_ok(d)) return SMHA_ERR_UNSUPPORTED;
     if ((plan->Bm != 1 && plan->Bm != B) || (plan->Hm != 1 && plan->Hm != H)) return SMHA_ERR_SHAPE;
     if ((int64_t)B * H > (1 << 24)) return SMHA_ERR_UNSUPPORTED;
     return SMHA_OK;
@@ -1431,11 +1452,12 @@ extern "C" smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H
         (void)hipGetLastError();
         return SMHA_ERR_HIP;
     }
+    const int D = kernel_head_size(d);
     for (int bf16 = 0; bf16 < 2; ++bf16) {  // (the two input types may run different forms of the kernel)
-        const int form = block_form(plan, d, bf16 != 0);
+        const int form = d == D ? block_form(plan, D, bf16 != 0) : 1;
         const smha_plan::Prepared *pr = nullptr;
         void *ws = nullptr;
-        const smha_status_t s2 = prepared_for(plan, B, H, d, grain_for(plan, B, H, d, form), form, &pr, &ws);
+        const smha_status_t s2 = prepared_for(plan, B, H, D, grain_for(plan, B, H, D, form), form, &pr, &ws);
         if (s2 != SMHA_OK) return s2;
     }
     return SMHA_OK;
@@ -1478,7 +1500,8 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
     if (!plan || !Q || !K || !V || !O || B < 1 || H < 1) return SMHA_ERR_INVALID_ARG;
     if (in_dtype != SMHA_F16 && in_dtype != SMHA_BF16) return SMHA_ERR_UNSUPPORTED;
     if (out_dtype != in_dtype && out_dtype != SMHA_F32) return SMHA_ERR_UNSUPPORTED;
-    if (d != 64 && d != 128) return SMHA_ERR_UNSUPPORTED;
+    if (!head_size_ok(d)) return SMHA_ERR_UNSUPPORTED;
+    const int D = kernel_head_size(d);
     if (kernel < SMHA_KERNEL_AUTO || kernel > SMHA_KERNEL_BLOCK) return SMHA_ERR_INVALID_ARG;
     if ((plan->Bm != 1 && plan->Bm != B) || (plan->Hm != 1 && plan->Hm != H)) return SMHA_ERR_SHAPE;
     if (!strides_ok(q_strides) || !strides_ok(k_strides) || !strides_ok(v_strides) || !strides_ok(o_strides))
@@ -1514,12 +1537,13 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
     fp.Q = (const uint16_t *)Q; fp.K = (const uint16_t *)K; fp.V = (const uint16_t *)V; fp.O = O;
     take(fp.qs, q_strides, S); take(fp.ks, k_strides, Sk); take(fp.vs, v_strides, Sk); take(fp.os, o_strides, S);
     fp.B = B; fp.H = H; fp.S = S; fp.Sk = Sk; fp.Bm = plan->Bm; fp.Hm = plan->Hm;
+    fp.d = d;
     fp.out_dtype = out_dtype;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
-    const int form = block_form(plan, d, in_dtype == SMHA_BF16);
-    const int lvl = grain_for(plan, B, H, d, form);
+    const int form = d == D ? block_form(plan, D, in_dtype == SMHA_BF16) : 1;
+    const int lvl = grain_for(plan, B, H, D, form);
     const WorkLists &wl = plan->lists[lvl];
     fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl];
     fp.uent = dv.uent; fp.gidx = dv.gidx; fp.n_gidx = (int)plan->h_gidx.size(); fp.kt_bitmap = dv.kt_bitmap; fp.bmp_spare = (int)(plan->h_kt_bitmap.size() / 64) - 1;
@@ -1533,7 +1557,7 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
         if ((int64_t)B * H * wl.max_items > ((int64_t)1 << 28)) return SMHA_ERR_UNSUPPORTED;  // (the order table indexes items with 32 bits)
         const smha_plan::Prepared *pr = nullptr;
         void *ws = nullptr;
-        const smha_status_t st = prepared_for(plan, B, H, d, lvl, form, &pr, &ws, !static_ws);
+        const smha_status_t st = prepared_for(plan, B, H, D, lvl, form, &pr, &ws, !static_ws);
         fp.form = form;
         if (st != SMHA_OK) return st;
         if (static_ws && pr->ws_bytes) {
@@ -1561,12 +1585,12 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
         fp.scratch = (float *)ws;
         fp.counters = ws ? (uint32_t *)((char *)ws + pr->counters_at) : nullptr;
         fp.max_splits = wl.max_split_rows;
-        if (d == 64)
+        if (D == 64)
             e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, fp, stream) : launch_block<64, false>(plan, fp, stream);
         else
             e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, fp, stream) : launch_block<128, false>(plan, fp, stream);
     } else {
-        if (d == 64)
+        if (D == 64)
             e = in_dtype == SMHA_BF16 ? launch_row<64, true>(plan, fp, stream) : launch_row<64, false>(plan, fp, stream);
         else
             e = in_dtype == SMHA_BF16 ? launch_row<128, true>(plan, fp, stream) : launch_row<128, false>(plan, fp, stream);

@@ -267,6 +267,47 @@ def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
         assert np.allclose(got[1, 1].astype(np.float64), W.bits_to_f64(V, dtype)[1, 1], rtol=1e-5, atol=1e-7)
 
 
+@pytest.mark.parametrize("kernel", ["block", "row"])
+@pytest.mark.parametrize("d,dtype", [(8, "f16"), (32, "f16"), (32, "bf16"), (40, "f16"), (80, "bf16"), (96, "f16"),
+                                     (96, "bf16"), (120, "f16")])
+def test_head_sizes_other_than_64_and_128(torch_mod, smha, kernel, d, dtype):
+    """Any multiple of 8 up to 128: the kernels for 64 and 128 columns run narrower heads (SURVEY's shape variants:
+    32 and 96).  Rows are packed, so a read or a store past a row's d columns would hit its neighbour."""
+    for S in (37, 257, 1000):
+        B, H = 2, 2
+        Q, K, V = W.qkv_bits(B, H, S, d, dtype, 1.0, 4000 + S + d)
+        rng = np.random.default_rng(S + d)
+        masks = (rng.random((B, H, S, S)) < 0.3).astype(np.uint8)
+        masks[0, 1] = 1                      # dense attention
+        masks[1, 0, S // 2] = 0              # one fully masked row
+        masks[1, 1] = np.eye(S, dtype=np.uint8)  # one key per row: O = V
+        for out_f32 in (True, False):
+            got = run_case(torch_mod, smha, Q, K, V, dtype, masks, KERNELS[kernel], out_f32=out_f32,
+                           what=f"head size {d} S={S} {dtype} {kernel} f32out={out_f32}")
+            assert np.all(got[1, 0, S // 2] == 0.0)
+    # split groups (partial results merged) and gathered tiles at a narrow head
+    if kernel == "block":
+        S = 2100
+        for spec, want in ((W.MaskSpec(flags=W.WINDOW | W.GLOBAL, window_left=32, window_right=32, n_global=70), "n_split_rows"),
+                           (W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=70, stride=37, stride_phase=5), "n_gathered")):
+            Q, K, V = W.qkv_bits(1, 2, S, d, dtype, 1.0, 77 + d)
+            masks = W.dense_mask(spec, 1, 2, S)
+            with smha.Plan.from_desc(spec, 1, 2, S, head_dim=d, force=smha.SMHA_KERNEL_BLOCK) as plan:
+                assert plan.info()[want] > 0
+                for out_f32 in (True, False):
+                    run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, plan=plan, out_f32=out_f32,
+                             what=f"head size {d} {want} f32out={out_f32}")
+
+
+def test_head_sizes_that_are_refused(torch_mod, smha):
+    masks = np.ones((1, 1, 64, 64), dtype=np.uint8)
+    with smha.Plan.from_dense(masks, head_dim=64) as plan:
+        for d in (4, 12, 100, 136, 256):
+            q = torch_mod.zeros(1, 1, 64, d, device="cuda", dtype=torch_mod.float16)
+            with pytest.raises(smha.SmhaError):
+                plan.forward(q, q, q)
+
+
 def test_random_shapes_masks_and_sharing(torch_mod, smha):
     """Seeded sweep over query / key counts around the tile edges, both head sizes and dtypes, masks shared
     or not across batch and heads, five mask families (unstructured at several densities, 64-blocky, band
