@@ -178,7 +178,7 @@ def test_error_paths_return_status_codes():
         st = lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 64, 0, 0,
                               None, None, None, None, 0.0, 0, None)
         assert st == 5
-        assert lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 48, 0, 0,
+        assert lib.smha_forward(ctypes.c_void_p(p.handle), addr, addr, addr, addr, 1, 1, 100, 0, 0,
                                 None, None, None, None, 0.0, 0, None) == 2
         assert lib.smha_forward(ctypes.c_void_p(p.handle), addr + 2, addr, addr, addr, 1, 1, 64, 0, 0,
                                 None, None, None, None, 0.0, 0, None) == 2
