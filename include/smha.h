@@ -15,8 +15,8 @@
  *     produces an all-zero output row (the paper does not define this case).
  *   - Self-attention has Sq = Sk = S; a dense mask may also have fewer or more queries than
  *     keys (smha_plan_from_dense_rect: cross-attention, a chunk of queries against cached
- *     keys).  head_dim d is a multiple of 8 up to 128 (heads narrower than 64 or 128 run on the
- *     kernel of that width, their missing columns read as zeros).  Q/K/V are IEEE binary16 or bfloat16.
+ *     keys).  head_dim d is a multiple of 8 up to 256 (the kernels exist for 64, 128 and 256
+ *     columns; a narrower head runs on the next of them, its missing columns read as zeros).  Q/K/V are IEEE binary16 or bfloat16.
  *   - All functions return a status code; nothing is printed, thrown or aborted.
  *     On error, output parameters are left untouched.
  *   - "host" / "device" is stated per pointer.  The library never frees or keeps

@@ -160,8 +160,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, in
 __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, int byte_off) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);  // out of range -> zeros
 }
-template <int D> __device__ __forceinline__ int swz_k(int row) { return (row / (128 / D)) & (D / 8 - 1); }
-template <int D> __device__ __forceinline__ int swz_v(int row) { return ((row / (128 / D)) & (D / 32 - 1)) << 2; }
+// (rows of 256 bytes or more: a row's chunks are permuted inside each aligned group of 16)
+template <int D> __device__ __forceinline__ int swz_k(int row) {
+    if constexpr (D >= 128) return row & 15;
+    else return (row / (128 / D)) & (D / 8 - 1);
+}
+template <int D> __device__ __forceinline__ int swz_v(int row) {
+    if constexpr (D >= 128) return (row & 3) << 2;
+    else return ((row / (128 / D)) & (D / 32 - 1)) << 2;
+}
 typedef __attribute__((address_space(3))) void lds_void;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -357,14 +364,14 @@ __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x
 // SPLIT: the plan cuts some 128-row groups into parts (the instantiation for plans that do not carries
 // none of the merge code: its registers would be paid for in every item's start and end).
 template <int D, bool BF16, int OUT, bool GATHER, bool SPLIT>
-__global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const FwdParams p) {
+__global__ void __launch_bounds__(256, D == 64 ? 4 : D == 128 ? 2 : 1) smha_block_fwd(const FwdParams p) {
     constexpr int NS = D / 16;            // k-steps of S^T = K Q^T
     constexpr int NDT = D / 32;           // 32-wide d tiles of O^T
     constexpr int TILE = 64 * D;          // one K or V tile, in elements
     constexpr int CPR = D / 8;            // 16-byte chunks per K/V row
     constexpr int LPW = CPR / 4;          // 1 KiB load instructions per wave, per tile, per tensor
     constexpr int NP = BF16 ? 2 : 1;      // P operands per product (hi, lo for bfloat16)
-    constexpr int PF = D == 128 ? 8 : 4;  // LDS fragment requests kept ahead of the MFMAs (d = 128 has the registers: 199 of 256;
+    constexpr int PF = D >= 128 ? 8 : 4;  // LDS fragment requests kept ahead of the MFMAs (d = 128 has the registers: 199 of 256;
                                           // 8 instead of 4 is worth 1.6 % there; at d = 64 more would spill)
     // K[0], K[1], V[0], V[1]: tile t lives in K[t & 1], V[t & 1]
     __shared__ __attribute__((aligned(1024))) uint16_t smem[4 * TILE];
@@ -446,24 +453,31 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
     // global -> LDS: wave w fills the 1 KiB blocks w, w+4, ... of each tile; LDS chunk (row, pc)
     // receives global chunk pc ^ swz(row).  Block w + 4 i starts 64 i / CPR * 4 rows (a multiple
     // of 16) below block w, which leaves the swizzle alone: one per-lane offset serves all i.
+    // (D = 256: the blocks are 8 rows apart, and the K swizzle of a wave's odd blocks differs from that of
+    // its even ones in bit 3: a second offset)
     constexpr int RSTEP = 4 * 64 / CPR;  // rows between two of a wave's blocks
+    constexpr int NKO = RSTEP % 16 ? 2 : 1;
     // A head narrower than D has no chunks d/8 .. CPR-1: a lane whose chunk is one of them carries kNoChunk
     // instead of its offset.  Offsets are unsigned 32-bit sums below 2^31 (the host checks the sizes), so with
     // kNoChunk added they stay past every buffer, the load returns zeros and a store is dropped.
     constexpr uint32_t kNoChunk = 0x80000000u;
     const int cpr_d = p.d >> 3;  // chunks a row has in memory
-    uint32_t k_go, v_go;
+    uint32_t k_go[NKO], v_go;  // (block i of the wave: k_go[i % NKO] + i RSTEP rows)
+    uint32_t g_kc[NKO], g_vc;  // with gathered tiles a staged row may come from any key: offset = key * pitch + chunk part
+    const int g_row = (w * 64 + lane) / CPR;  // the lane's row in the wave's first block
     {
         const int pchunk = w * 64 + lane;
         const int row = pchunk / CPR, pc = pchunk % CPR;
-        const int kc = pc ^ swz_k<D>(row), vc = pc ^ swz_v<D>(row);
-        k_go = kc < cpr_d ? (uint32_t)(row * ksb + kc * 16) : kNoChunk;
+        const int vc = pc ^ swz_v<D>(row);
         v_go = vc < cpr_d ? (uint32_t)(row * vsb + vc * 16) : kNoChunk;
+        g_vc = vc < cpr_d ? (uint32_t)(vc * 16) : kNoChunk;
+#pragma unroll
+        for (int o = 0; o < NKO; ++o) {
+            const int kc = pc ^ swz_k<D>(row + o * RSTEP);
+            k_go[o] = kc < cpr_d ? (uint32_t)(row * ksb + kc * 16) : kNoChunk;
+            g_kc[o] = kc < cpr_d ? (uint32_t)(kc * 16) : kNoChunk;
+        }
     }
-    // With gathered tiles a staged row may come from any key: offset = key * pitch + chunk part.
-    const int g_row = (w * 64 + lane) / CPR;  // the lane's row in the wave's first block
-    const uint32_t g_kc = k_go == kNoChunk ? kNoChunk : k_go - (uint32_t)(g_row * ksb);
-    const uint32_t g_vc = v_go == kNoChunk ? kNoChunk : v_go - (uint32_t)(g_row * vsb);
     const uint32_t gix_lds = (uint32_t)(uintptr_t)(lds_void *)gix;
 
     // state of the item being started / computed
@@ -525,14 +539,14 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             }
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, g_kc + (wk.n > 0 ? key[i] * ksb : OOB));
+                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, g_kc[i % NKO] + (wk.n > 0 ? key[i] * ksb : OOB));
                 load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, g_vc + (wk.n > 0 ? key[i] * vsb : OOB));
             }
         } else {
             const int kb = wk.n > 0 ? wk.col0 * 64 * ksb : OOB, vb = wk.n > 0 ? wk.col0 * 64 * vsb : OOB;
 #pragma unroll
             for (int i = 0; i < LPW; ++i) {
-                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, k_go + (kb + i * RSTEP * ksb));
+                load_to_lds(rK, smem_base + (w + 4 * i) * 1024, k_go[i % NKO] + (kb + i * RSTEP * ksb));
                 load_to_lds(rV, smem_base + 2 * TB + (w + 4 * i) * 1024, v_go + (vb + i * RSTEP * vsb));
             }
         }
@@ -590,11 +604,11 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
             if (i & 1)
                 load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 1024, g_vc + (ld_live ? ld_key[i >> 1] * vsb : OOB));
             else
-                load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, g_kc + (ld_live ? ld_key[i >> 1] * ksb : OOB));
+                load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, g_kc[(i >> 1) % NKO] + (ld_live ? ld_key[i >> 1] * ksb : OOB));
         } else if (i & 1)
             load_to_lds(rV, Vd + (w + 4 * (i >> 1)) * 1024, v_go + (ld_vb + (i >> 1) * RSTEP * vsb));
         else
-            load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, k_go + (ld_kb + (i >> 1) * RSTEP * ksb));
+            load_to_lds(rK, Kd + (w + 4 * (i >> 1)) * 1024, k_go[(i >> 1) % NKO] + (ld_kb + (i >> 1) * RSTEP * ksb));
     };
 
     u32x4 qf[NS];  // Q^T operand: lane (j, hh) holds Q[q0 + j][16 s + 8 hh .. +8], read from the slab below
@@ -713,9 +727,13 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : 2) smha_block_fwd(const Fwd
                 o[dt] = mfma32<BF16>(vfrag[i % PF], pf[cu][0], o[dt]);
                 if constexpr (BF16) o[dt] = mfma32<BF16>(vfrag[i % PF], pf[cu][1], o[dt]);
                 if (i + PF < 4 * NDT) vfrag[i % PF] = v_frag(i + PF);
-                if (cu < 3) {
+                if (cu < 3) {  // the next key group's four pairs, spread over this group's MFMAs
+                    if constexpr (NDT <= 4) {
 #pragma unroll
-                    for (int q = dt * (4 / NDT); q < (dt + 1) * (4 / NDT); ++q) p_pair(cu + 1, q, gs);
+                        for (int q = dt * (4 / NDT); q < (dt + 1) * (4 / NDT); ++q) p_pair(cu + 1, q, gs);
+                    } else {
+                        if (dt % (NDT / 4) == 0) p_pair(cu + 1, dt / (NDT / 4), gs);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -871,13 +889,14 @@ __device__ __forceinline__ float dpp_add(float v) {
     return v + __builtin_bit_cast(float, moved);
 }
 
-// sum over the aligned group of LPK (8 or 16) lanes; every lane of the group gets the sum
+// sum over the aligned group of LPK (8, 16 or 32) lanes; every lane of the group gets the sum
 template <int LPK>
 __device__ __forceinline__ float group_sum(float v) {
     v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
     v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
     v = dpp_add<0x141>(v);  // row_half_mirror: the other quad of the 8
-    if constexpr (LPK == 16) v = dpp_add<0x140>(v);  // row_mirror: the other half of the 16
+    if constexpr (LPK >= 16) v = dpp_add<0x140>(v);  // row_mirror: the other half of the 16
+    if constexpr (LPK == 32) v += __shfl_xor(v, 16);  // the other 16 of the 32
     return v;
 }
 
@@ -1253,16 +1272,16 @@ static int block_form(const smha_plan *plan, int d, bool bf16) {
         const char *e = getenv("SMHA_BLOCK_FORM");
         return e ? atoi(e) : 0;
     }();
-    if (plan->n_gathered > 0 || (bf16 && d == 128)) return 1;
+    if (plan->n_gathered > 0 || (bf16 && d == 128) || d > 128) return 1;
     const int asked = plan->opts.block_form ? plan->opts.block_form : from_env;
     return asked == 2 ? 2 : 1;
 }
-static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : 2); }
+static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : d == 128 ? 2 : 1); }
 
 template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
     if (fp.n_work == 0) return hipSuccess;
-    if constexpr (!(BF16 && D == 128)) {
+    if constexpr (!(BF16 && D == 128) && D <= 128) {
         if (fp.form == 2) {
             hipLaunchKernelGGL((smha_block_fwd2<D, BF16, OUT>), dim3(8u * (unsigned)fp.per_xcd), dim3(512), 0, stream, fp);
             return hipGetLastError();
@@ -1298,11 +1317,12 @@ static hipError_t launch_row(const smha_plan *plan, FwdParams &fp, hipStream_t s
     const int groups = (BH + 7) / 8;
     // rows with few keys share a wave (see the kernel): decided from the mean row length of the plan
     const bool short_rows = plan->row_mean_nnz <= 32.0;
-    const int rows_per_wg = short_rows ? 16 : 4;
+    constexpr int RPW = D <= 128 ? 4 : 2;  // rows of a wave when rows are short (a row needs D / 8 lanes per key)
+    const int rows_per_wg = short_rows ? 4 * RPW : 4;
     fp.wgs_per_bh = (fp.S + rows_per_wg - 1) / rows_per_wg;
     const unsigned grid = (unsigned)(8 * groups * fp.wgs_per_bh);
     if (short_rows)
-        hipLaunchKernelGGL((smha_row_fwd<D, BF16, 4>), dim3(grid), dim3(256), 0, stream, fp);
+        hipLaunchKernelGGL((smha_row_fwd<D, BF16, RPW>), dim3(grid), dim3(256), 0, stream, fp);
     else
         hipLaunchKernelGGL((smha_row_fwd<D, BF16, 1>), dim3(grid), dim3(256), 0, stream, fp);
     return hipGetLastError();
@@ -1429,10 +1449,10 @@ static smha_status_t prepared_for(const smha_plan *plan, int B, int H, int d, in
     return SMHA_OK;
 }
 
-// Head sizes: any multiple of 8 up to 128.  The kernels exist for 64 and 128 columns; a narrower head
-// runs on the next of the two, its missing columns read as zeros (which changes no score) and never stored.
-static bool head_size_ok(int d) { return d >= 8 && d <= 128 && d % 8 == 0; }
-static int kernel_head_size(int d) { return d <= 64 ? 64 : 128; }
+// Head sizes: any multiple of 8 up to 256.  The kernels exist for 64, 128 and 256 columns; a narrower head
+// runs on the next of the three, its missing columns read as zeros (which changes no score) and never stored.
+static bool head_size_ok(int d) { return d >= 8 && d <= 256 && d % 8 == 0; }
+static int kernel_head_size(int d) { return d <= 64 ? 64 : d <= 128 ? 128 : 256; }
 
 static smha_status_t check_shape(const smha_plan *plan, int B, int H, int d) {
     if (!plan || B < 1 || H < 1) return SMHA_ERR_INVALID_ARG;
@@ -1587,13 +1607,17 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
         fp.max_splits = wl.max_split_rows;
         if (D == 64)
             e = in_dtype == SMHA_BF16 ? launch_block<64, true>(plan, fp, stream) : launch_block<64, false>(plan, fp, stream);
-        else
+        else if (D == 128)
             e = in_dtype == SMHA_BF16 ? launch_block<128, true>(plan, fp, stream) : launch_block<128, false>(plan, fp, stream);
+        else
+            e = in_dtype == SMHA_BF16 ? launch_block<256, true>(plan, fp, stream) : launch_block<256, false>(plan, fp, stream);
     } else {
         if (D == 64)
             e = in_dtype == SMHA_BF16 ? launch_row<64, true>(plan, fp, stream) : launch_row<64, false>(plan, fp, stream);
-        else
+        else if (D == 128)
             e = in_dtype == SMHA_BF16 ? launch_row<128, true>(plan, fp, stream) : launch_row<128, false>(plan, fp, stream);
+        else
+            e = in_dtype == SMHA_BF16 ? launch_row<256, true>(plan, fp, stream) : launch_row<256, false>(plan, fp, stream);
     }
     return e == hipSuccess ? SMHA_OK : SMHA_ERR_HIP;
 }

@@ -361,7 +361,7 @@ smha_status_t check_opts(const smha_plan_opts_t *in, smha_plan_opts_t &o) {
     if (o.device_id < -2) return SMHA_ERR_INVALID_ARG;
     if (o.block_form < 0 || o.block_form > 2) return SMHA_ERR_INVALID_ARG;
     if (o.head_dim == 0) o.head_dim = 64;
-    if (o.head_dim < 8 || o.head_dim > 128 || o.head_dim % 8) return SMHA_ERR_UNSUPPORTED;
+    if (o.head_dim < 8 || o.head_dim > 256 || o.head_dim % 8) return SMHA_ERR_UNSUPPORTED;
     return SMHA_OK;
 }
 
@@ -405,8 +405,9 @@ static double eq1_threshold(double valid16, int Sq, int Sk) {
 struct CostModel {
     double step_ns, fixed_ns, entry_ns, row_ns;
 };
-static CostModel cost_model(int d, double mean_row_nnz) {  // (a head narrower than 64 or 128 columns costs what that kernel costs)
+static CostModel cost_model(int d, double mean_row_nnz) {  // (a head narrower than 64, 128 or 256 columns costs what that kernel costs)
     const bool shared = mean_row_nnz <= 32.0;
+    if (d > 128) return CostModel{14.0, 60.0, 0.039, shared ? 0.12 : 0.43};  // (256 columns: one workgroup per compute unit)
     return d > 64 ? CostModel{4.5, 60.0, 0.0195, shared ? 0.12 : 0.43} : CostModel{2.8, 60.0, 0.0096, shared ? 0.13 : 0.44};
 }
 

@@ -269,10 +269,10 @@ def test_ragged_lengths_and_degenerate_rows(torch_mod, smha, kernel, d, dtype):
 
 @pytest.mark.parametrize("kernel", ["block", "row"])
 @pytest.mark.parametrize("d,dtype", [(8, "f16"), (32, "f16"), (32, "bf16"), (40, "f16"), (80, "bf16"), (96, "f16"),
-                                     (96, "bf16"), (120, "f16")])
+                                     (96, "bf16"), (120, "f16"), (136, "bf16"), (192, "f16"), (256, "f16"), (256, "bf16")])
 def test_head_sizes_other_than_64_and_128(torch_mod, smha, kernel, d, dtype):
-    """Any multiple of 8 up to 128: the kernels for 64 and 128 columns run narrower heads (SURVEY's shape variants:
-    32 and 96).  Rows are packed, so a read or a store past a row's d columns would hit its neighbour."""
+    """Any multiple of 8 up to 256: the kernels for 64, 128 and 256 columns run narrower heads (SURVEY's shape
+    variants: 32, 96 and 256).  Rows are packed, so a read or a store past a row's d columns would hit its neighbour."""
     for S in (37, 257, 1000):
         B, H = 2, 2
         Q, K, V = W.qkv_bits(B, H, S, d, dtype, 1.0, 4000 + S + d)
@@ -302,7 +302,7 @@ def test_head_sizes_other_than_64_and_128(torch_mod, smha, kernel, d, dtype):
 def test_head_sizes_that_are_refused(torch_mod, smha):
     masks = np.ones((1, 1, 64, 64), dtype=np.uint8)
     with smha.Plan.from_dense(masks, head_dim=64) as plan:
-        for d in (4, 12, 100, 136, 256):
+        for d in (4, 12, 100, 260, 264, 512):
             q = torch_mod.zeros(1, 1, 64, d, device="cuda", dtype=torch_mod.float16)
             with pytest.raises(smha.SmhaError):
                 plan.forward(q, q, q)
