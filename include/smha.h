@@ -67,8 +67,10 @@ typedef struct {
     int block_form; /* which form of the block-wise kernel runs where both exist: 0 = the library's choice,
                        1 = four waves per workgroup, every wave forms scores, probabilities and output of
                        its rows (two to four workgroups per compute unit); 2 = eight waves per workgroup,
-                       score waves and value waves, one workgroup per compute unit.  Plans with gathered
-                       tiles, and bfloat16 at d = 128, always run form 1.  For measurements and tests.   */
+                       score waves and value waves, one workgroup per compute unit; 3 = eight waves of 16
+                       rows per workgroup, two workgroups per compute unit (128 columns only).  Plans with
+                       gathered tiles always run form 1, as does bfloat16 at d = 128 where form 2 is asked
+                       for.  For measurements and tests.                                                 */
 } smha_plan_opts_t;
 
 /* Mask description: the atomic patterns of the paper (Sec. 2.1.2, Fig. 1) and their

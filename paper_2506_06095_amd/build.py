@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsmha.so")
 SOURCES = ["plan.cpp", "kernels.hip"]
-HEADERS = ["smha_internal.hpp", "block_fwd2.inc", os.path.join(ROOT, "include", "smha.h")]
+HEADERS = ["smha_internal.hpp", "block_fwd2.inc", "block_fwd16.inc", os.path.join(ROOT, "include", "smha.h")]
 
 
 def hipcc() -> str:

@@ -61,8 +61,8 @@ struct FwdParams {
     int n_gidx;           // entries of gidx
     const uint64_t *kt_bitmap;
     int bmp_spare;  // index of an all-zero spare bitmap block (what fetch_word falls back to for a tile without a bitmap)
-    // split 128-row groups: workspace slots of 128 D + 512 floats per (batch*head), arrival counters
-    // (4 per (batch*head, split group), zero between launches), and the groups' descriptions
+    // split 128-row groups: workspace slots of 128 D + 1024 floats per (batch*head), arrival counters
+    // (8 per (batch*head, split group), zero between launches), and the groups' descriptions
     float *scratch;
     uint32_t *counters;
     int max_slots, max_splits;
@@ -236,27 +236,31 @@ __device__ __forceinline__ void store4(void *O, int64_t elem_off, float a, float
 // wave waits for its stores before it counts itself in: when the counter reads count - 1, every other
 // part's quarter is in memory.  The wave that finds it so owns the merge: it leaves its mark (its
 // workgroup's number) in the counter and merges when it sees fit (merge_split_parts).
+// The same for the kernel form whose eight waves own 16 rows each (an eighth of the group per wave): Acc is
+// the accumulator vector (16 floats there, 4 here), NA how many a lane holds; a slot has room for eight
+// waves' references and sums, and a group has eight counters, whichever form runs.
 constexpr uint32_t kMergeMark = 0x80000000u;
-template <int D>
-__device__ __forceinline__ bool put_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
+constexpr int kSlotExtra = 1024;  // floats of a workspace slot after the 128 x D accumulators: 512 references, 512 sums
+template <int D, typename Acc, int NA>
+__device__ __forceinline__ bool put_split_part(const FwdParams &p, const Acc (&o)[NA], float m_c, float l_tot,
                                                int w, int lane, int b, int h, int bh, int slot, int split) {
-    constexpr int NDT = D / 32;
-    constexpr int NR = 16 * NDT;                     // accumulator registers per lane
-    constexpr size_t SLOT = (size_t)(128 * D + 512);  // floats per workspace slot
+    constexpr int E = sizeof(Acc) / 4;
+    constexpr int NR = E * NA;                                 // accumulator registers per lane
+    constexpr size_t SLOT = (size_t)(128 * D + kSlotExtra);  // floats per workspace slot
     float *mine = p.scratch + ((size_t)bh * p.max_slots + slot) * SLOT;
     auto put = [&](float *ptr, float v) __attribute__((always_inline)) {
         __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
 #pragma unroll
-    for (int dt = 0; dt < NDT; ++dt)
+    for (int dt = 0; dt < NA; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) put(mine + ((size_t)w * NR + dt * 16 + r) * 64 + lane, o[dt][r]);
+        for (int r = 0; r < E; ++r) put(mine + ((size_t)w * NR + dt * E + r) * 64 + lane, o[dt][r]);
     put(mine + 128 * D + w * 64 + lane, m_c);
-    put(mine + 128 * D + 256 + w * 64 + lane, l_tot);
+    put(mine + 128 * D + 512 + w * 64 + lane, l_tot);
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0): the stores above have completed
     const int mask = (p.Bm > 1 ? b : 0) * p.Hm + (p.Hm > 1 ? h : 0);
     const int count = uniform_load(&p.split_rows[uniform_load(p.split_off + mask) + split].count);
-    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
+    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 8 + w;
     int last = 0;
     if (lane == 0) {
         const uint32_t seen = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -270,18 +274,18 @@ __device__ __forceinline__ bool put_split_part(const FwdParams &p, const f32x16 
 // returns at once): all parts in list order (the owner's included, re-read: the result does not depend on
 // which part came last), then O; the counter goes back to zero for the next launch.
 // (owner_known: the caller remembers put_split_part's answer, and the counter need not be asked)
-template <int D, int OUT, int PB, int RB>  // a batch of loads in flight: PB parts x RB accumulator registers
+// (W16: the eight-wave form: register r of a lane is column 16 (r / 4) + 4 (lane / 16) + r % 4 of its row)
+template <int D, int OUT, int PB, int RB, bool W16 = false>  // a batch of loads in flight: PB parts x RB accumulator registers
 __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int lane, int b, int h, int bh, int qrow, int split,
                                                   bool owner_known = false) {
-    constexpr int NDT = D / 32;
-    constexpr int NR = 16 * NDT;
-    constexpr size_t SLOT = (size_t)(128 * D + 512);
+    constexpr int NR = W16 ? D / 4 : D / 2;
+    constexpr size_t SLOT = (size_t)(128 * D + kSlotExtra);
     const int hh = lane >> 5;
     const float NEG_INF = -__builtin_inff();
     auto get = [&](const float *ptr) __attribute__((always_inline)) {
         return __hip_atomic_load(const_cast<float *>(ptr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
-    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 4 + w;
+    uint32_t *counter = p.counters + ((size_t)bh * p.max_splits + split) * 8 + w;
     if (!owner_known) {
         uint32_t state = 0;
         if (lane == 0) state = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -321,7 +325,7 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
             for (int u = 0; u < PB; ++u) {
                 at[u] = (c0 + u < sr.count ? c0 + u : c0) * (int)SLOT;
                 mu[u] = get(base + at[u] + 128 * D + w * 64 + lane);
-                if (r0 == 0) lu[u] = get(base + at[u] + 128 * D + 256 + w * 64 + lane);
+                if (r0 == 0) lu[u] = get(base + at[u] + 128 * D + 512 + w * 64 + lane);
             }
 #pragma unroll
             for (int u = 0; u < PB; ++u)
@@ -344,9 +348,9 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
         if (qrow < p.S) {
 #pragma unroll
             for (int i = 0; i < RB; i += 4) {
-                const int r = r0 + i, dt = r >> 4, g4 = (r & 15) >> 2;
-                if (32 * dt + 8 * g4 + 4 * hh < p.d)
-                    store4<OUT>(p.O, obase + 32 * dt + 8 * g4 + 4 * hh, acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
+                const int r = r0 + i;
+                const int col = W16 ? 16 * (r >> 2) + 4 * (lane >> 4) : 32 * (r >> 4) + 8 * ((r & 15) >> 2) + 4 * hh;
+                if (col < p.d) store4<OUT>(p.O, obase + col, acc[i] * inv, acc[i + 1] * inv, acc[i + 2] * inv, acc[i + 3] * inv);
             }
         }
     }
@@ -357,7 +361,7 @@ __device__ __forceinline__ void merge_split_parts(const FwdParams &p, int w, int
 template <int D, int OUT>
 __device__ __forceinline__ void finish_split_part(const FwdParams &p, const f32x16 (&o)[D / 32], float m_c, float l_tot,
                                                   int w, int lane, int b, int h, int bh, int qrow, int slot, int split) {
-    if (put_split_part<D>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split))
+    if (put_split_part<D, f32x16, D / 32>(p, o, m_c, l_tot, w, lane, b, h, bh, slot, split))
         merge_split_parts<D, OUT, 4, 8>(p, w, lane, b, h, bh, qrow, split, true);
 }
 
@@ -841,7 +845,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : D == 128 ? 2 : 1) smha_bloc
             if constexpr (SPLIT) {
                 // (which of its items' groups this wave has to merge is kept as one bit per turn; from turn 63
                 // on the bit only says that the counters of those turns have to be asked)
-                const bool last = put_split_part<D>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh,
+                const bool last = put_split_part<D, f32x16, NDT>(p, o, m_run * p.c /* -inf stays -inf (c > 0) */, l_tot, w, lane, b, h, bh,
                                                     item.slot, item.split);
                 if (last || turn >= 63) owned |= 1ull << min(turn, 63);
             }
@@ -879,6 +883,7 @@ __global__ void __launch_bounds__(256, D == 64 ? 4 : D == 128 ? 2 : 1) smha_bloc
 }
 
 #include "block_fwd2.inc"
+#include "block_fwd16.inc"
 
 // ---------------------------------------------------------------------------------------
 // Row-wise kernel
@@ -1272,8 +1277,10 @@ static int block_form(const smha_plan *plan, int d, bool bf16) {
         const char *e = getenv("SMHA_BLOCK_FORM");
         return e ? atoi(e) : 0;
     }();
-    if (plan->n_gathered > 0 || (bf16 && d == 128) || d > 128) return 1;
     const int asked = plan->opts.block_form ? plan->opts.block_form : from_env;
+    if (plan->n_gathered > 0 || d > 128) return 1;
+    if (asked == 3) return d == 128 ? 3 : 1;  // eight waves of 16 rows: 128 columns only
+    if (bf16 && d == 128) return 1;
     return asked == 2 ? 2 : 1;
 }
 static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : d == 128 ? 2 : 1); }
@@ -1291,6 +1298,15 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     // registers); the work order was made for exactly this many workgroups
     const unsigned grid = 8u * (unsigned)fp.per_xcd;
     const bool split = fp.max_slots > 0;
+    if constexpr (D == 128) {
+        if (fp.form == 3) {  // eight waves of 16 rows (plans without gathered tiles)
+            if (split)
+                hipLaunchKernelGGL((smha_block_fwd16<D, BF16, OUT, true>), dim3(grid), dim3(512), 0, stream, fp);
+            else
+                hipLaunchKernelGGL((smha_block_fwd16<D, BF16, OUT, false>), dim3(grid), dim3(512), 0, stream, fp);
+            return hipGetLastError();
+        }
+    }
     if (plan->n_gathered > 0) {
         if (split)
             hipLaunchKernelGGL((smha_block_fwd<D, BF16, OUT, true, true>), dim3(grid), dim3(256), 0, stream, fp);

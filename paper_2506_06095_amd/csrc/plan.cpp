@@ -359,7 +359,7 @@ smha_status_t check_opts(const smha_plan_opts_t *in, smha_plan_opts_t &o) {
     if (o.selector != SMHA_SELECTOR_CALIBRATED && o.selector != SMHA_SELECTOR_PAPER_EQ1)
         return SMHA_ERR_INVALID_ARG;
     if (o.device_id < -2) return SMHA_ERR_INVALID_ARG;
-    if (o.block_form < 0 || o.block_form > 2) return SMHA_ERR_INVALID_ARG;
+    if (o.block_form < 0 || o.block_form > 3) return SMHA_ERR_INVALID_ARG;
     if (o.head_dim == 0) o.head_dim = 64;
     if (o.head_dim < 8 || o.head_dim > 256 || o.head_dim % 8) return SMHA_ERR_UNSUPPORTED;
     return SMHA_OK;
@@ -726,10 +726,10 @@ smha_status_t finish_plan(smha_plan *p) {
 // four arrival counters (one per 32-row quarter) per (batch*head, split group).
 size_t workspace_bytes(const smha_plan *plan, int lvl, int B, int H, int d, size_t *counters_at) {
     const WorkLists &wl = plan->lists[plan->fine_differs ? lvl : 0];
-    const size_t partials = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 512) * sizeof(float);
+    const size_t partials = (size_t)B * H * wl.max_slots * (size_t)(128 * d + 1024) * sizeof(float);
     const size_t at = (partials + 255) / 256 * 256;
     if (counters_at) *counters_at = at;
-    return at + (size_t)B * H * wl.max_split_rows * 4 * sizeof(uint32_t);
+    return at + (size_t)B * H * wl.max_split_rows * 8 * sizeof(uint32_t);
 }
 
 // The block kernel's work order for B x H heads on `slots` resident workgroups per XCD.  Items
