@@ -64,7 +64,8 @@ typedef struct {
     int no_gather;  /* nonzero: the block kernel visits every non-empty 64x64 tile as it is; 0: tiles
                        with few used key columns are repacked into gathered tiles (block kernel
                        work lists only; the exported formats are never affected)               */
-    int block_form; /* which form of the block-wise kernel runs where both exist: 0 = the library's choice,
+    int block_form; /* which form of the block-wise kernel runs where several exist: 0 = the library's choice
+                       (at 128 columns form 3, unless nearly all tiles are full and the lists long: form 1),
                        1 = four waves per workgroup, every wave forms scores, probabilities and output of
                        its rows (two to four workgroups per compute unit); 2 = eight waves per workgroup,
                        score waves and value waves, one workgroup per compute unit; 3 = eight waves of 16

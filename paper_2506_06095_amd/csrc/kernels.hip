@@ -1280,10 +1280,11 @@ static int block_form(const smha_plan *plan, int d, bool bf16) {
     const int asked = plan->opts.block_form ? plan->opts.block_form : from_env;
     if (plan->n_gathered > 0 || d > 128) return 1;
     if (asked == 3) return d == 128 ? 3 : 1;  // eight waves of 16 rows: 128 columns only
+    if (asked == 0) return d == 128 && !plan->dense_long_lists ? 3 : 1;  // the library's choice
     if (bf16 && d == 128) return 1;
     return asked == 2 ? 2 : 1;
 }
-static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : (d == 64 ? 4 : d == 128 ? 2 : 1); }
+static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : form == 3 ? 2 : (d == 64 ? 4 : d == 128 ? 2 : 1); }
 
 template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
@@ -1299,7 +1300,9 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     const unsigned grid = 8u * (unsigned)fp.per_xcd;
     const bool split = fp.max_slots > 0;
     if constexpr (D == 128) {
-        if (fp.form == 3) {  // eight waves of 16 rows (plans without gathered tiles)
+        if (fp.form == 3) {  // eight waves of 16 rows (plans without gathered tiles; at 64 columns the form also
+                             // works, but fits two workgroups per compute unit where the first form fits four,
+                             // and was 10-20 % slower on every mask measured: not instantiated)
             if (split)
                 hipLaunchKernelGGL((smha_block_fwd16<D, BF16, OUT, true>), dim3(grid), dim3(512), 0, stream, fp);
             else
@@ -1490,7 +1493,8 @@ extern "C" smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H
     }
     const int D = kernel_head_size(d);
     for (int bf16 = 0; bf16 < 2; ++bf16) {  // (the two input types may run different forms of the kernel)
-        const int form = d == D ? block_form(plan, D, bf16 != 0) : 1;
+        int form = block_form(plan, D, bf16 != 0);
+        if (form == 2 && d != D) form = 1;  // (the second form has no narrower heads)
         const smha_plan::Prepared *pr = nullptr;
         void *ws = nullptr;
         const smha_status_t s2 = prepared_for(plan, B, H, D, grain_for(plan, B, H, D, form), form, &pr, &ws);
@@ -1578,7 +1582,8 @@ static smha_status_t forward_impl(const smha_plan_t *plan, const void *Q, const 
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)d);
     fp.c = sc * 1.4426950408889634f;
     const DeviceArrays &dv = plan->dev;
-    const int form = d == D ? block_form(plan, D, in_dtype == SMHA_BF16) : 1;
+    int form = block_form(plan, D, in_dtype == SMHA_BF16);
+    if (form == 2 && d != D) form = 1;  // (the second form has no narrower heads)
     const int lvl = grain_for(plan, B, H, D, form);
     const WorkLists &wl = plan->lists[lvl];
     fp.items = dv.items[lvl]; fp.item_off = dv.item_off[lvl]; fp.item_cnt = dv.item_cnt[lvl];
@@ -1662,5 +1667,10 @@ extern "C" const char *smha_kernel_name(const smha_plan_t *plan, int d, smha_dty
                                         smha_kernel_t kernel) {
     if (!plan) return "";
     const int which = kernel == SMHA_KERNEL_AUTO ? plan->kernel : (int)kernel;
-    return which == SMHA_KERNEL_ROW ? "smha_row_fwd" : "smha_block_fwd";
+    if (which == SMHA_KERNEL_ROW) return "smha_row_fwd";
+    if (!head_size_ok(d)) return "smha_block_fwd";
+    const int D = kernel_head_size(d);
+    int form = block_form(plan, D, in_dtype == SMHA_BF16);
+    if (form == 2 && d != D) form = 1;
+    return form == 3 ? "smha_block_fwd16" : form == 2 ? "smha_block_fwd2" : "smha_block_fwd";
 }

@@ -118,6 +118,9 @@ struct smha_plan {
     // longest list is the whole launch).  smha_forward picks by how many items the call has.
     smha::WorkLists lists[2];
     bool fine_differs = false;  // false: [1] is empty and [0] serves both
+    // Tiles almost all full and lists long (dense causal and the like): at 128 columns such plans run the
+    // block kernel's first form; all others its third form, whose waves skip at 16 rows x 32 keys.
+    bool dense_long_lists = false;
     int64_t n_gathered = 0;
 
     int device = -1;  // -1: nothing uploaded

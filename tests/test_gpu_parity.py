@@ -746,22 +746,26 @@ def test_second_form_ragged_and_split(torch_mod, smha, S, d, dtype):
             run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, plan=plan, what=f"form 2 ragged {S} f16 out")
 
 
-def test_third_form_of_the_block_kernel_on_config_5(torch_mod, smha):
-    """The block kernel's third form (eight waves of 16 rows, asked for with the plan option) on the headline
-    workload: every head against the oracle, both output types, and the padded rows exactly zero."""
+@pytest.mark.parametrize("form", [1, 3])
+def test_first_and_third_form_of_the_block_kernel_on_config_5(torch_mod, smha, form):
+    """The block kernel's first form (four waves of 32 rows) and third form (eight waves of 16 rows), each asked
+    for with the plan option, on the headline workload: every head against the oracle, both output types, and
+    the padded rows exactly zero.  (Left to itself the library runs the third form here.)"""
     c = W.config(5)
     Q, K, V = W.qkv_bits(c.B, c.H, c.S, c.d, c.dtype, c.std, c.seed)
     masks = W.dense_mask(c.mask, c.B, c.H, c.S)
-    with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, head_dim=c.d, force=smha.SMHA_KERNEL_BLOCK, block_form=3) as plan:
+    with smha.Plan.from_desc(c.mask, c.B, c.H, c.S, block=c.block, head_dim=c.d, force=smha.SMHA_KERNEL_BLOCK, block_form=form) as plan:
         assert plan.info()["n_gathered"] == 0 and plan.info()["n_split_rows"] > 0
+        assert smha.smha_kernel_name(plan.handle, c.d, smha.SMHA_F16) == ("smha_block_fwd16" if form == 3 else "smha_block_fwd")
         for out_f32 in (False, True):
-            got = run_case(torch_mod, smha, Q, K, V, c.dtype, masks, 0, out_f32=out_f32, plan=plan, what=f"{c.name}/form 3")
+            got = run_case(torch_mod, smha, Q, K, V, c.dtype, masks, 0, out_f32=out_f32, plan=plan, what=f"{c.name}/form {form}")
             assert np.all(got[:, :, c.mask.valid_len[0]:, :] == 0.0)
 
 
+@pytest.mark.parametrize("form", [1, 3])
 @pytest.mark.parametrize("S,d,dtype", [(100, 128, "f16"), (130, 128, "bf16"), (1000, 96, "f16"), (2500, 128, "f16"), (2500, 120, "bf16")])
-def test_third_form_ragged_and_split(torch_mod, smha, S, d, dtype):
-    """Third form at ragged lengths, with empty 128-row groups, fully masked rows, part tiles, heads narrower
+def test_first_and_third_form_ragged_and_split(torch_mod, smha, S, d, dtype, form):
+    """Both forms at ragged lengths, with empty 128-row groups, fully masked rows, part tiles, heads narrower
     than 128 and (at 2500) groups that are split between workgroups."""
     B, H = 2, 3
     Q, K, V = W.qkv_bits(B, H, S, d, dtype, 1.0, seed=S + d)
@@ -772,10 +776,10 @@ def test_third_form_ragged_and_split(torch_mod, smha, S, d, dtype):
     masks[0, 1] = (rng.random((S, S)) < 0.3) & (jj <= ii)                       # scattered causal: part tiles everywhere
     masks[0, 1, S // 2] = 0                                                    # a query without keys
     masks[0, 2, : S // 3, : S // 2] = 1                                        # full tiles, and query groups with nothing at all
-    with smha.Plan.from_dense(masks, head_dim=d, force=smha.SMHA_KERNEL_BLOCK, no_gather=True, block_form=3) as plan:
-        got = run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, out_f32=True, plan=plan, what=f"form 3 ragged {S}")
+    with smha.Plan.from_dense(masks, head_dim=d, force=smha.SMHA_KERNEL_BLOCK, no_gather=True, block_form=form) as plan:
+        got = run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, out_f32=True, plan=plan, what=f"form {form} ragged {S}")
         assert np.all(got[:, 1, S // 2] == 0.0) and np.all(got[:, 2, S // 3:] == 0.0)
-        run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, plan=plan, what=f"form 3 ragged {S} 16-bit out")
+        run_case(torch_mod, smha, Q, K, V, dtype, masks, 0, plan=plan, what=f"form {form} ragged {S} 16-bit out")
 
 
 def test_plan_that_holds_only_the_row_format(torch_mod, smha):
