@@ -29,12 +29,13 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel: constants copied from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # summaries under profiles/ (runs of this very command, scaled by what the same counters read for a 256 MiB device
 # copy: FETCH_SIZE x2.0, WRITE_SIZE x1.0 on this machine).  This run does not measure them; the line says so.
-MEASURED_TRAFFIC = {
-    ("cfg5_bigbird_8k", "block"): {"read_bytes": 310.2e6, "write_bytes": 82.3e6},
-    ("cfg4_random_blocks", "block"): {"read_bytes": 50.8e6, "write_bytes": 16.8e6},
-    ("cfg3_strided_causal", "row"): {"read_bytes": 59.1e6, "write_bytes": 16.8e6},
-    ("cfg3_strided_causal", "block"): {"read_bytes": 57.7e6, "write_bytes": 19.9e6},
-    ("scattered_2048_k8", "row"): {"read_bytes": 51.1e6, "write_bytes": 16.8e6},
+MEASURED_TRAFFIC = {  # (workload, kernel as smha_kernel_name gives it)
+    ("cfg5_bigbird_8k", "smha_block_fwd16"): {"read_bytes": 329.2e6, "write_bytes": 82.8e6},
+    ("cfg5_bigbird_8k", "smha_block_fwd"): {"read_bytes": 310.2e6, "write_bytes": 82.3e6},
+    ("cfg4_random_blocks", "smha_block_fwd"): {"read_bytes": 50.8e6, "write_bytes": 16.8e6},
+    ("cfg3_strided_causal", "smha_row_fwd"): {"read_bytes": 59.1e6, "write_bytes": 16.8e6},
+    ("cfg3_strided_causal", "smha_block_fwd"): {"read_bytes": 57.7e6, "write_bytes": 19.9e6},
+    ("scattered_2048_k8", "smha_row_fwd"): {"read_bytes": 51.1e6, "write_bytes": 16.8e6},
 }
 
 
@@ -185,7 +186,7 @@ def main() -> int:
                 "kernel": smha.smha_kernel_name(plan.handle, d, 0 if c.dtype == "f16" else 1),
                 "bytes_per_launch": alg_bytes, "launch_ms": launch_ms}
 
-    tr = MEASURED_TRAFFIC.get((c.name, kernel))
+    tr = MEASURED_TRAFFIC.get((c.name, roof["kernel"]))
     if tr is not None:
         roof["traffic"] = tr["read_bytes"] + tr["write_bytes"]
         roof["traffic_detail"] = dict(tr, unit="bytes per launch",
