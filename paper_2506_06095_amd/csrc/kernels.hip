@@ -1152,45 +1152,99 @@ smha_status_t classify_device_mask(const uint8_t *dev_mask, int n_masks, int Sq,
     const long long per_mask = (long long)nqt * nkt, n_tiles = per_mask * n_masks;
     info.resize((size_t)n_tiles);
     part_bits.assign((size_t)n_masks, {});
-    TileInfo *d_info = nullptr;
-    uint64_t *d_bits = nullptr;
-    uint32_t *d_cnt = nullptr;
-    auto fail = [&](smha_status_t st) {
+    // One scratch allocation {tile records, per-mask counters, bitmap slots}; it is kept for the next plan
+    // (allocating and freeing tens of megabytes costs more than the analysis) unless it is very large.
+    const size_t info_bytes = (size_t)n_tiles * sizeof(TileInfo), cnt_bytes = ((size_t)n_masks * 4 + 255) / 256 * 256;
+    const size_t bits_at = (info_bytes + cnt_bytes + 255) / 256 * 256, total = bits_at + (size_t)n_tiles * 512;
+    static std::mutex cache_mutex;
+    static void *cache_ptr = nullptr;
+    static size_t cache_bytes = 0;
+    static int cache_device = -1;
+    constexpr size_t kKeepAtMost = (size_t)128 << 20;
+    std::lock_guard<std::mutex> lock(cache_mutex);  // (also serialises analyses that share the scratch)
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) {
         (void)hipGetLastError();
-        (void)hipFree(d_info); (void)hipFree(d_bits); (void)hipFree(d_cnt);
+        return SMHA_ERR_HIP;
+    }
+    char *scratch_dev = nullptr;
+    bool cached = false;
+    if (cache_ptr && cache_device == device && cache_bytes >= total) {
+        scratch_dev = (char *)cache_ptr;
+        cached = true;
+    } else {
+        if (cache_ptr && total <= kKeepAtMost) {  // replaced by a larger one below
+            int prev = device;
+            (void)hipSetDevice(cache_device);
+            (void)hipFree(cache_ptr);
+            (void)hipSetDevice(prev);
+            cache_ptr = nullptr;
+            cache_bytes = 0;
+        }
+        if (hipMalloc(reinterpret_cast<void **>(&scratch_dev), total) != hipSuccess) {
+            (void)hipGetLastError();
+            return SMHA_ERR_ALLOC;
+        }
+        if (total <= kKeepAtMost) {
+            cache_ptr = scratch_dev;
+            cache_bytes = total;
+            cache_device = device;
+            cached = true;
+        }
+    }
+    TileInfo *d_info = reinterpret_cast<TileInfo *>(scratch_dev);
+    uint32_t *d_cnt = reinterpret_cast<uint32_t *>(scratch_dev + info_bytes);
+    uint64_t *d_bits = reinterpret_cast<uint64_t *>(scratch_dev + bits_at);
+    auto done = [&](smha_status_t st) {
+        if (st != SMHA_OK) (void)hipGetLastError();
+        if (!cached) (void)hipFree(scratch_dev);
         return st;
     };
-    if (hipMalloc(reinterpret_cast<void **>(&d_info), (size_t)n_tiles * sizeof(TileInfo)) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&d_bits), (size_t)n_tiles * 512) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void **>(&d_cnt), (size_t)n_masks * 4) != hipSuccess)
-        return fail(SMHA_ERR_ALLOC);
-    if (hipMemsetAsync(d_cnt, 0, (size_t)n_masks * 4, 0) != hipSuccess) return fail(SMHA_ERR_HIP);
+    if (hipMemsetAsync(d_cnt, 0, (size_t)n_masks * 4, 0) != hipSuccess) return done(SMHA_ERR_HIP);
     const unsigned grid = (unsigned)((n_tiles + 3) / 4);
     hipLaunchKernelGGL(smha_mask_classify, dim3(grid), dim3(256), 0, 0, dev_mask, d_info, d_bits, d_cnt, Sq, Sk, nqt, nkt, n_tiles);
-    if (hipGetLastError() != hipSuccess) return fail(SMHA_ERR_HIP);
+    if (hipGetLastError() != hipSuccess) return done(SMHA_ERR_HIP);
+    // (tile records and counters are adjacent: one copy)
+    std::vector<char> back(info_bytes + (size_t)n_masks * 4);
+    if (hipMemcpy(back.data(), scratch_dev, back.size(), hipMemcpyDeviceToHost) != hipSuccess) return done(SMHA_ERR_HIP);
+    std::memcpy(info.data(), back.data(), info_bytes);
     std::vector<uint32_t> n_part((size_t)n_masks);
-    if (hipMemcpy(info.data(), d_info, (size_t)n_tiles * sizeof(TileInfo), hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(n_part.data(), d_cnt, (size_t)n_masks * 4, hipMemcpyDeviceToHost) != hipSuccess)
-        return fail(SMHA_ERR_HIP);
+    std::memcpy(n_part.data(), back.data() + info_bytes, (size_t)n_masks * 4);
     for (int mi = 0; mi < n_masks; ++mi) {
         if (!n_part[mi]) continue;
         part_bits[mi].resize((size_t)n_part[mi] * 64);
         if (hipMemcpy(part_bits[mi].data(), d_bits + (size_t)mi * per_mask * 64, (size_t)n_part[mi] * 512,
                       hipMemcpyDeviceToHost) != hipSuccess)
-            return fail(SMHA_ERR_HIP);
+            return done(SMHA_ERR_HIP);
     }
-    (void)hipFree(d_info); (void)hipFree(d_bits); (void)hipFree(d_cnt);
-    return SMHA_OK;
+    return done(SMHA_OK);
 }
 
-template <typename T>
-static bool to_device(T *&dst, const std::vector<T> &src) {
-    dst = nullptr;
-    const size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
-    if (hipMalloc(reinterpret_cast<void **>(&dst), bytes) != hipSuccess) return false;
-    if (!src.empty() && hipMemcpy(dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess)
-        return false;
-    return true;
+// Every index array of a plan lives in one device allocation, filled with one copy: a plan has up to 18
+// arrays, and an allocation and a copy each cost more than the analysis of a small mask.
+struct Arena {
+    std::vector<char> host;
+    std::vector<std::pair<void **, size_t>> fixups;  // (pointer to set, offset)
+    template <typename T>
+    void add(T *&dst, const std::vector<T> &src) {
+        const size_t at = (host.size() + 255) / 256 * 256;
+        host.resize(at + std::max<size_t>(src.size(), 1) * sizeof(T));
+        if (!src.empty()) std::memcpy(host.data() + at, src.data(), src.size() * sizeof(T));
+        fixups.push_back({reinterpret_cast<void **>(&dst), at});
+    }
+};
+
+static int compute_units_of(int device_id) {
+    static std::mutex m;
+    static int cached[64] = {0};
+    std::lock_guard<std::mutex> lock(m);
+    if (device_id >= 0 && device_id < 64 && cached[device_id]) return cached[device_id];
+    hipDeviceProp_t prop;
+    int n = hipGetDeviceProperties(&prop, device_id) == hipSuccess ? prop.multiProcessorCount : 256;
+    if (n < 8) n = 8;
+    n = (n + 7) / 8 * 8;
+    if (device_id >= 0 && device_id < 64) cached[device_id] = n;
+    return n;
 }
 
 smha_status_t upload_plan(smha_plan *p, int device_id) {
@@ -1204,32 +1258,40 @@ smha_status_t upload_plan(smha_plan *p, int device_id) {
         (void)hipGetLastError();
         return SMHA_ERR_HIP;
     }
-    bool ok = true;
     DeviceArrays &d = p->dev;
     p->device = device_id;
-    {
-        hipDeviceProp_t prop;
-        p->n_cu = hipGetDeviceProperties(&prop, device_id) == hipSuccess ? prop.multiProcessorCount : 256;
-        if (p->n_cu < 8) p->n_cu = 8;
-        p->n_cu = (p->n_cu + 7) / 8 * 8;
-    }
+    p->n_cu = compute_units_of(device_id);
+    Arena arena;
     if (p->has_row) {
-        ok = ok && to_device(d.row_ptr, p->h_row_ptr) && to_device(d.col_idx, p->h_col_idx) &&
-             to_device(d.col_off, p->h_col_off);
+        arena.add(d.row_ptr, p->h_row_ptr);
+        arena.add(d.col_idx, p->h_col_idx);
+        arena.add(d.col_off, p->h_col_off);
     }
-    if (ok && p->has_block) {
-        ok = to_device(d.uent, p->h_uent) && to_device(d.gidx, p->h_gidx) && to_device(d.kt_bitmap, p->h_kt_bitmap);
-        for (int lvl = 0; ok && lvl < (p->fine_differs ? 2 : 1); ++lvl) {
+    if (p->has_block) {
+        arena.add(d.uent, p->h_uent);
+        arena.add(d.gidx, p->h_gidx);
+        arena.add(d.kt_bitmap, p->h_kt_bitmap);
+        for (int lvl = 0; lvl < (p->fine_differs ? 2 : 1); ++lvl) {
             const WorkLists &wl = p->lists[lvl];
-            ok = to_device(d.items[lvl], wl.items) &&
-                 to_device(d.item_off[lvl], wl.item_off) && to_device(d.item_cnt[lvl], wl.item_cnt) &&
-                 to_device(d.split_rows[lvl], wl.split_rows) && to_device(d.split_off[lvl], wl.split_off) &&
-                 to_device(d.split_cnt[lvl], wl.split_cnt);
+            arena.add(d.items[lvl], wl.items);
+            arena.add(d.item_off[lvl], wl.item_off);
+            arena.add(d.item_cnt[lvl], wl.item_cnt);
+            arena.add(d.split_rows[lvl], wl.split_rows);
+            arena.add(d.split_off[lvl], wl.split_off);
+            arena.add(d.split_cnt[lvl], wl.split_cnt);
         }
+    }
+    bool ok = true;
+    if (!arena.host.empty()) {
+        ok = hipMalloc(&d.arena, arena.host.size()) == hipSuccess &&
+             hipMemcpy(d.arena, arena.host.data(), arena.host.size(), hipMemcpyHostToDevice) == hipSuccess;
+        if (ok)
+            for (auto &f : arena.fixups) *f.first = (char *)d.arena + f.second;
     }
     (void)hipSetDevice(prev);
     if (!ok) {
         (void)hipGetLastError();
+        for (auto &f : arena.fixups) *f.first = nullptr;
         release_device(p);
         return SMHA_ERR_ALLOC;
     }
@@ -1242,11 +1304,7 @@ void release_device(smha_plan *p) {
     (void)hipGetDevice(&prev);
     (void)hipSetDevice(p->device);
     DeviceArrays &d = p->dev;
-    void *ptrs[] = {d.row_ptr, d.col_idx, d.col_off, d.uent, d.gidx, d.kt_bitmap,
-                    d.items[0], d.item_off[0], d.item_cnt[0], d.split_rows[0], d.split_off[0], d.split_cnt[0],
-                    d.items[1], d.item_off[1], d.item_cnt[1], d.split_rows[1], d.split_off[1], d.split_cnt[1]};
-    for (void *q : ptrs)
-        if (q) (void)hipFree(q);
+    if (d.arena) (void)hipFree(d.arena);
     d = DeviceArrays{};
     for (smha_plan::Prepared *pr : p->prepared) {
         if (pr->order) (void)hipFree(pr->order);

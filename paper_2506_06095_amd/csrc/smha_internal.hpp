@@ -71,6 +71,7 @@ struct SplitRow {
 };
 
 struct DeviceArrays {
+    void *arena = nullptr;        // the one allocation every array below is a part of
     // row path
     int32_t *row_ptr = nullptr;   // [n_masks][S+1], offsets local to the mask
     int32_t *col_idx = nullptr;   // concatenated
