@@ -257,8 +257,8 @@ smha_status_t smha_forward_static(const smha_plan_t *plan, const void *Q, const 
  * size on a plan that runs the block-wise kernel (Sec. 4.2.2): the work order (which workgroup
  * takes which work item, see smha_plan_work_order) and 4 workspaces that hold the partial results
  * of 128-row groups whose tile lists were split between workgroups (those are merged inside the
- * same launch by whichever part finishes last) -- B*H * (split parts per head) * (128 d + 512)
- * floats each; plans that split nothing get none.  Allocates device memory and copies to it
+ * same launch by whichever part finishes last) -- B*H * (split parts per head) * (128 D + 1024)
+ * floats each, D the kernel width for d (64, 128 or 256); plans that split nothing get none.  Allocates device memory and copies to it
  * (blocking); call it outside stream capture, on the plan's device.  Calling it again for the
  * same shape does nothing; plans that run the row-wise kernel need nothing and return SMHA_OK.
  * Errors: INVALID_ARG, UNSUPPORTED (d, more than 2^28 work items), SHAPE, ALLOC, HIP. */
