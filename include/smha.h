@@ -258,15 +258,15 @@ smha_status_t smha_forward_static(const smha_plan_t *plan, const void *Q, const 
  * takes which work item, see smha_plan_work_order) and 4 workspaces that hold the partial results
  * of 128-row groups whose tile lists were split between workgroups (those are merged inside the
  * same launch by whichever part finishes last) -- B*H * (split parts per head) * (128 D + 1024)
- * floats each, D the kernel width for d (64, 128 or 256); plans that split nothing get none.  Allocates device memory and copies to it
- * (blocking); call it outside stream capture, on the plan's device.  Calling it again for the
+ * floats each, D the kernel width for d (64, 128 or 256); plans that split nothing get none.
+ * Allocates device memory and copies to it (blocking); call it outside stream capture, on the plan's device.  Calling it again for the
  * same shape does nothing; plans that run the row-wise kernel need nothing and return SMHA_OK.
  * Errors: INVALID_ARG, UNSUPPORTED (d, more than 2^28 work items), SHAPE, ALLOC, HIP. */
 smha_status_t smha_plan_prepare(const smha_plan_t *plan, int B, int H, int d);
 
 /* The block kernel's work order for B x H heads when workgroups_per_xcd workgroups are
- * resident on each of the chip's 8 XCDs (smha_forward uses 2 per compute unit at d = 128,
- * 4 at d = 64): the plan's work items (the workgroup tiling of Algorithm 1's outer loop)
+ * resident on each of the chip's 8 XCDs (smha_forward uses 4 per compute unit at 64 columns,
+ * 2 at 128, 1 at 256): the plan's work items (the workgroup tiling of Algorithm 1's outer loop)
  * differ in length, and each head's items go, longest first, to the workgroup with the
  * least work so far.  For inspection and tests; runs on the host.
  *   fine       0: the items of SMHA_EXPORT_KERNEL_ITEMS, 1: those of KERNEL_ITEMS_FINE
