@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = BigBird, seq 8192)")
     ap.add_argument("--kernel", choices=["auto", "row", "block"], default="auto")
+    ap.add_argument("--block-form", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="which form of the block kernel runs where several exist (0 = the library's choice)")
     ap.add_argument("--scattered", type=int, default=0, metavar="K",
                     help="instead of --config: a scattered mask (K pseudo-random keys per query plus the diagonal), batch 4, "
                          "16 heads, sequence 2048, head size 64, fp16 -- the ground on which the selector takes the "
@@ -98,20 +100,20 @@ def main() -> int:
     force = {"auto": smha.SMHA_KERNEL_AUTO, "row": smha.SMHA_KERNEL_ROW, "block": smha.SMHA_KERNEL_BLOCK}[args.kernel]
     if scattered is not None:
         t0 = time.perf_counter()
-        plan = smha.Plan.from_dense(scattered, block=c.block, head_dim=d, force=force)
+        plan = smha.Plan.from_dense(scattered, block=c.block, head_dim=d, force=force, block_form=args.block_form)
         plan_ms = (time.perf_counter() - t0) * 1e3
     elif args.dense_device_mask:
         dense = W.dense_mask(c.mask, B, H, S)
         dev_mask = torch.from_numpy(dense).cuda()
-        smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force).close()   # warm-up (first launch)
+        smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force, block_form=args.block_form).close()   # warm-up (first launch)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        plan = smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force)
+        plan = smha.Plan.from_dense(dev_mask, block=c.block, head_dim=d, force=force, block_form=args.block_form)
         plan_ms = (time.perf_counter() - t0) * 1e3
         del dev_mask, dense
     else:
         t0 = time.perf_counter()
-        plan = smha.Plan.from_desc(c.mask, B, H, S, block=c.block, head_dim=d, force=force)
+        plan = smha.Plan.from_desc(c.mask, B, H, S, block=c.block, head_dim=d, force=force, block_form=args.block_form)
         plan_ms = (time.perf_counter() - t0) * 1e3
     info = plan.info()
     n_masks = info["Bm"] * info["Hm"]
