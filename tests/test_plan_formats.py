@@ -406,3 +406,29 @@ def test_kernel_work_lists_with_gathered_tiles_cover_the_mask_exactly_once(name)
                     assert cnt[Sq:].sum() == 0 and cnt[:, Sk:].sum() == 0
         for k in ("load_row_ptr", "load_col_idx", "flags", "bitmap"):  # the exported formats do not change
             assert np.array_equal(p.export(k), q.export(k))
+
+
+def test_which_form_of_the_block_kernel_a_plan_runs():
+    """The library's own choice at 128 columns (host-only plans: nothing runs): the form with eight waves of 16
+    rows, except for plans whose tiles are nearly all full and whose lists are long (dense causal), and except
+    for plans with gathered tiles; at 64 and 256 columns the first form; the plan option overrides."""
+    c5 = W.config(5)
+    cases = [
+        (c5.mask, 1, 2, 8192, 128, {}, "smha_block_fwd16"),
+        (W.MaskSpec(flags=W.CAUSAL), 1, 2, 4096, 128, {}, "smha_block_fwd"),        # full tiles, lists of 32 steps
+        (W.MaskSpec(flags=W.CAUSAL), 1, 2, 1024, 128, {}, "smha_block_fwd16"),      # short lists
+        (W.MaskSpec(flags=W.WINDOW, window_left=32, window_right=32), 1, 2, 4096, 128, {}, "smha_block_fwd16"),
+        (W.MaskSpec(flags=W.WINDOW, window_left=32, window_right=32), 1, 2, 4096, 96, {}, "smha_block_fwd16"),
+        (c5.mask, 1, 2, 8192, 64, {}, "smha_block_fwd"),
+        (c5.mask, 1, 2, 8192, 256, {}, "smha_block_fwd"),
+        (c5.mask, 1, 2, 8192, 128, {"block_form": 1}, "smha_block_fwd"),
+        (c5.mask, 1, 2, 8192, 128, {"block_form": 2}, "smha_block_fwd2"),
+        (W.MaskSpec(flags=W.CAUSAL), 1, 2, 4096, 128, {"block_form": 3}, "smha_block_fwd16"),
+        (W.MaskSpec(flags=W.CAUSAL | W.WINDOW | W.STRIDED, window_left=70, stride=37, stride_phase=5), 1, 2, 2048, 128, {}, "smha_block_fwd"),
+    ]
+    for spec, B, H, S, d, extra, want in cases:
+        with smha.Plan.from_desc(spec, B, H, S, head_dim=d, device_id=-2, force=smha.SMHA_KERNEL_BLOCK, **extra) as plan:
+            got = smha.smha_kernel_name(plan.handle, d, smha.SMHA_F16)
+            assert got == want, (spec, S, d, extra, got, want)
+    with smha.Plan.from_desc(c5.mask, 1, 2, 8192, head_dim=128, device_id=-2, force=smha.SMHA_KERNEL_ROW) as plan:
+        assert smha.smha_kernel_name(plan.handle, 128, smha.SMHA_F16) == "smha_row_fwd"
