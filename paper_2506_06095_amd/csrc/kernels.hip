@@ -1336,13 +1336,14 @@ static int block_form(const smha_plan *plan, int d, bool bf16) {
         return e ? atoi(e) : 0;
     }();
     const int asked = plan->opts.block_form ? plan->opts.block_form : from_env;
-    if (plan->n_gathered > 0 || d > 128) return 1;
-    if (asked == 3) return d == 128 ? 3 : 1;  // eight waves of 16 rows: 128 columns only
+    if (plan->n_gathered > 0) return 1;
+    if (d > 128) return asked == 1 ? 1 : 3;  // 256 columns: eight waves of 16 rows are two waves per SIMD, four of 32 are one
+    if (asked == 3) return d == 128 ? 3 : 1;  // eight waves of 16 rows: 128 and 256 columns
     if (asked == 0) return d == 128 && !plan->dense_long_lists ? 3 : 1;  // the library's choice
     if (bf16 && d == 128) return 1;
     return asked == 2 ? 2 : 1;
 }
-static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : form == 3 ? 2 : (d == 64 ? 4 : d == 128 ? 2 : 1); }
+static int workgroups_per_cu(int form, int d) { return form == 2 ? 1 : form == 3 ? (d > 128 ? 1 : 2) : (d == 64 ? 4 : d == 128 ? 2 : 1); }
 
 template <int D, bool BF16, int OUT>
 static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStream_t stream) {
@@ -1357,7 +1358,7 @@ static hipError_t launch_block_out(const smha_plan *plan, FwdParams &fp, hipStre
     // registers); the work order was made for exactly this many workgroups
     const unsigned grid = 8u * (unsigned)fp.per_xcd;
     const bool split = fp.max_slots > 0;
-    if constexpr (D == 128) {
+    if constexpr (D >= 128) {
         if (fp.form == 3) {  // eight waves of 16 rows (plans without gathered tiles; at 64 columns the form also
                              // works, but fits two workgroups per compute unit where the first form fits four,
                              // and was 10-20 % slower on every mask measured: not instantiated)

@@ -407,7 +407,7 @@ struct CostModel {
 };
 static CostModel cost_model(int d, double mean_row_nnz) {  // (a head narrower than 64, 128 or 256 columns costs what that kernel costs)
     const bool shared = mean_row_nnz <= 32.0;
-    if (d > 128) return CostModel{12.5, 60.0, 0.039, shared ? 0.12 : 0.43};  // (256 columns, one workgroup per compute unit: 11.3-12.7 ns per step measured; the row constants are twice those of 128 columns, not measured)
+    if (d > 128) return CostModel{10.0, 60.0, 0.039, shared ? 0.12 : 0.43};  // (256 columns, one workgroup of eight waves per compute unit: 9.9-10.0 ns per step measured; the row constants are twice those of 128 columns, not measured)
     return d > 64 ? CostModel{4.5, 60.0, 0.0195, shared ? 0.12 : 0.43} : CostModel{2.8, 60.0, 0.0096, shared ? 0.13 : 0.44};
 }
 

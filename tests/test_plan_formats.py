@@ -411,7 +411,8 @@ def test_kernel_work_lists_with_gathered_tiles_cover_the_mask_exactly_once(name)
 def test_which_form_of_the_block_kernel_a_plan_runs():
     """The library's own choice at 128 columns (host-only plans: nothing runs): the form with eight waves of 16
     rows, except for plans whose tiles are nearly all full and whose lists are long (dense causal), and except
-    for plans with gathered tiles; at 64 and 256 columns the first form; the plan option overrides."""
+    for plans with gathered tiles; at 256 columns always that form unless tiles are gathered; at 64 columns the
+    first form; the plan option overrides."""
     c5 = W.config(5)
     cases = [
         (c5.mask, 1, 2, 8192, 128, {}, "smha_block_fwd16"),
@@ -420,7 +421,8 @@ def test_which_form_of_the_block_kernel_a_plan_runs():
         (W.MaskSpec(flags=W.WINDOW, window_left=32, window_right=32), 1, 2, 4096, 128, {}, "smha_block_fwd16"),
         (W.MaskSpec(flags=W.WINDOW, window_left=32, window_right=32), 1, 2, 4096, 96, {}, "smha_block_fwd16"),
         (c5.mask, 1, 2, 8192, 64, {}, "smha_block_fwd"),
-        (c5.mask, 1, 2, 8192, 256, {}, "smha_block_fwd"),
+        (c5.mask, 1, 2, 8192, 256, {}, "smha_block_fwd16"),
+        (c5.mask, 1, 2, 8192, 256, {"block_form": 1}, "smha_block_fwd"),
         (c5.mask, 1, 2, 8192, 128, {"block_form": 1}, "smha_block_fwd"),
         (c5.mask, 1, 2, 8192, 128, {"block_form": 2}, "smha_block_fwd2"),
         (W.MaskSpec(flags=W.CAUSAL), 1, 2, 4096, 128, {"block_form": 3}, "smha_block_fwd16"),
