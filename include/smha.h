@@ -65,13 +65,14 @@ typedef struct {
                        with few used key columns are repacked into gathered tiles (block kernel
                        work lists only; the exported formats are never affected)               */
     int block_form; /* which form of the block-wise kernel runs where several exist: 0 = the library's choice
-                       (at 128 columns form 3, unless nearly all tiles are full and the lists long: form 1),
+                       (at 128 columns form 3, unless nearly all tiles are full and the lists long: form 1;
+                       at 256 columns form 3; at 64 columns form 1),
                        1 = four waves per workgroup, every wave forms scores, probabilities and output of
-                       its rows (two to four workgroups per compute unit); 2 = eight waves per workgroup,
-                       score waves and value waves, one workgroup per compute unit; 3 = eight waves of 16
-                       rows per workgroup, two workgroups per compute unit (128 columns only).  Plans with
-                       gathered tiles always run form 1, as does bfloat16 at d = 128 where form 2 is asked
-                       for.  For measurements and tests.                                                 */
+                       its 32 rows (one to four workgroups per compute unit); 2 = eight waves per workgroup,
+                       score waves and value waves, one workgroup per compute unit (64 and 128 columns);
+                       3 = eight waves of 16 rows per workgroup, two workgroups per compute unit at 128
+                       columns, one at 256.  Plans with gathered tiles always run form 1, as does bfloat16
+                       at 128 columns where form 2 is asked for.  For measurements and tests.             */
 } smha_plan_opts_t;
 
 /* Mask description: the atomic patterns of the paper (Sec. 2.1.2, Fig. 1) and their
