@@ -88,7 +88,7 @@ struct DeviceArrays {
 };
 
 // The block kernel's work items for every mask of a plan: each 128-row group's list of steps, whole
-// or cut into parts whose partial results the merge kernel combines.
+// or cut into parts whose partial results are merged inside the same launch (see put_split_part in kernels.hip).
 struct WorkLists {
     std::vector<Item> items;
     std::vector<int32_t> item_off, item_cnt;
